@@ -1,0 +1,131 @@
+"""Reference for the CPU/GPU subgroup planner.  TEST INFRASTRUCTURE ONLY: pure
+Python, shares nothing with the HIP library, imported only by the tests.
+
+Three pieces:
+
+* ``stride_k``      -- the closed form of the performance model (Section 4.2, Eq. 1).
+* ``stride_targets`` / ``run_update_trace`` -- the placement rule and the action
+  order of the scheduling algorithm (Section 4.3, Algorithm 1).
+* ``phase_cost`` / ``brute_force_plan`` -- this build's own makespan estimate for
+  an arbitrary CPU/GPU assignment and its exhaustive minimiser, used to bound
+  the gap of the library's "balanced" planner.  The estimate is not from the
+  paper; it extends the same balance (host update time vs. link time vs. GPU
+  time) to unequal subgroup sizes, separate link rates per direction and a
+  fused host downscale.
+
+Pins (tests/test_plan_pins.py): the paper's second-machine worked example
+(Section 5.4: B=3, U_g=35, U_c=2, D_c=8.7 G params/s gives stride 2), "k=2 means
+every alternate subgroup" (Sections 5.3, 5.4), the 8-subgroup timeline of the
+update figure (33 % on the GPU, two static residents placed last; Section 4.1),
+independence of k from the subgroup size (Section 4.2), and the balance identity
+of Eq. 1 itself.
+"""
+from __future__ import annotations
+
+import itertools
+from typing import Iterable, List, Sequence, Tuple
+
+ON_CPU, ON_GPU = 0, 1
+
+
+def stride_k_real(B: float, U_g: float, U_c: float, D_c: float) -> float:
+    """Eq. 1 solved for k.  All four rates are in FP32 parameters per second:
+    B the host link (each direction), U_g / U_c the GPU / CPU update rates, D_c
+    the host FP32->16-bit downscale rate."""
+    return (3.0 / B + 1.0 / U_g) / (1.0 / U_c + 1.0 / D_c - 1.0 / (2.0 * B))
+
+
+def stride_k(B: float, U_g: float, U_c: float, D_c: float) -> int:
+    """The integer stride handed to Algorithm 1.  The paper rounds its worked
+    example 2.294 to 2; this build reads that as round-to-nearest, at least 1.
+    A non-positive denominator means the host never becomes the bottleneck in
+    the model: everything stays on the CPU except as forced, expressed here as
+    an infinite stride (0 is returned as the 'no GPU subgroup' marker)."""
+    den = 1.0 / U_c + 1.0 / D_c - 1.0 / (2.0 * B)
+    if den <= 0.0:
+        return 0
+    k = stride_k_real(B, U_g, U_c, D_c)
+    return max(1, int(k + 0.5))
+
+
+def stride_targets(n_sg: int, k: int, residents: Iterable[int] = ()) -> List[int]:
+    """Algorithm 1's test: subgroup i (0-based) goes to the GPU if it is a
+    static resident or if (i+1) is a multiple of the stride k."""
+    R = set(residents)
+    return [ON_GPU if (i in R or (k >= 1 and (i + 1) % k == 0)) else ON_CPU for i in range(n_sg)]
+
+
+def run_update_trace(n_sg: int, k: int, residents: Iterable[int] = ()) -> List[Tuple]:
+    """Algorithm 1 as a list of actions, in issue order.  Actions:
+    ("gpu_update", i), ("cpu_downscale", [subgroups queued so far]),
+    ("flush_out", j), ("prefetch_in", j), ("cpu_update", i).
+    prev_on_gpu / next_on_gpu are the nearest GPU-scheduled, non-resident
+    subgroups before / after i; when none exists the action is omitted."""
+    R = set(residents)
+    tgt = stride_targets(n_sg, k, R)
+    trace: List[Tuple] = []
+    queue: List[int] = []
+    for i in range(n_sg):
+        if i in R or (k >= 1 and (i + 1) % k == 0):
+            trace.append(("gpu_update", i))
+            trace.append(("cpu_downscale", list(queue)))
+            continue
+        elif i not in R and k >= 1 and i % k == 0:
+            prev = [j for j in range(i - 1, -1, -1) if tgt[j] == ON_GPU and j not in R]
+            nxt = [j for j in range(i + 1, n_sg) if tgt[j] == ON_GPU and j not in R]
+            if prev:
+                trace.append(("flush_out", prev[0]))
+            if nxt:
+                trace.append(("prefetch_in", nxt[0]))
+        trace.append(("cpu_update", i))
+        queue.append(i)
+    return trace
+
+
+# --------------------------------------------------------------------------
+# This build's makespan estimate for an arbitrary assignment.
+# --------------------------------------------------------------------------
+
+def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d2h_Bps: float,
+               gpu_params_per_s: float, cpu_params_per_s: float, launch_overhead_s: float,
+               n_slots: int) -> Tuple[float, float]:
+    """(predicted_s, lower_bound_s) of one update phase.
+
+    CPU-planned subgroups cost n/U_c on the host and 2 bytes/param of H2D for the
+    refreshed 16-bit parameters; GPU-planned ones cost 12 bytes/param each way
+    (p, m, v in FP32) and n/U_g + launch on the GPU.  With two or more staging
+    slots the three lanes overlap and only the first prefetch and its kernel are
+    exposed in front of the D2H lane; with a single slot prefetch, kernel and
+    flush of every GPU subgroup run back to back."""
+    assert len(sizes) == len(target)
+    n_g = [n for n, t in zip(sizes, target) if t == ON_GPU]
+    n_c = [n for n, t in zip(sizes, target) if t == ON_CPU]
+    N_G, N_C = float(sum(n_g)), float(sum(n_c))
+    h2d_bytes = 12.0 * N_G + 2.0 * N_C
+    d2h_bytes = 12.0 * N_G
+    t_h2d = h2d_bytes / h2d_Bps
+    t_d2h = d2h_bytes / d2h_Bps
+    t_cpu = N_C / cpu_params_per_s
+    t_gpu = N_G / gpu_params_per_s + launch_overhead_s * len(n_g)
+    if not n_g:
+        lane = t_h2d
+    elif n_slots >= 2:
+        first = n_g[0]
+        lead = 12.0 * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s
+        lane = max(t_h2d, lead + t_d2h, t_gpu)
+    else:
+        lane = 12.0 * N_G / h2d_Bps + t_gpu + t_d2h
+        lane = max(lane, t_h2d)
+    predicted = max(t_cpu, lane)
+    lower = max(t_h2d, t_d2h)
+    return predicted, lower
+
+
+def brute_force_plan(sizes: Sequence[int], **cost) -> Tuple[float, List[int]]:
+    """Exhaustive minimum of ``phase_cost`` over all 2^n assignments (n <= ~14)."""
+    best, best_t = None, None
+    for bits in itertools.product((ON_CPU, ON_GPU), repeat=len(sizes)):
+        c, _ = phase_cost(sizes, bits, **cost)
+        if best is None or c < best:
+            best, best_t = c, list(bits)
+    return best, best_t
