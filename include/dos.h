@@ -1,0 +1,236 @@
+/*
+ * libdos -- the optimizer-update hot path of "Deep Optimizer States"
+ * (arXiv 2410.21316) for one AMD MI355X (gfx950) GPU and its host cores.
+ *
+ * Plain C ABI: raw pointers (each documented as host or device), sizes and
+ * status codes.  No function throws, aborts or prints.  Unless stated
+ * otherwise, validation precedes work: when a call returns an error no element
+ * of any caller array has been modified.  The library never allocates or pins
+ * memory inside dos_adam_step / dos_adam_step_host / dos_run_update_phase
+ * (Section 4.1: interleaving must not incur allocation costs; all host buffers
+ * are pre-allocated and pre-pinned) -- staging memory and streams are handed in
+ * at context creation.
+ *
+ * The update (Sections 1, 2 "mixed precision", 4.1: FP32 parameters, momentum
+ * and variance; 16-bit gradients in, 16-bit parameter copy out; Adam).  The
+ * paper prints no equations; this library implements bias-corrected Adam with
+ * decoupled weight decay, every per-element operation one IEEE binary32
+ * operation rounded to nearest-even, unfused, gradual underflow:
+ *
+ *   scalars, once per call, formed in double and rounded to binary32 once:
+ *     step_size    = lr / (1 - beta1^step)
+ *     inv_sqrt_bc2 = 1 / sqrt(1 - beta2^step)
+ *     decay        = 1 - lr * weight_decay
+ *     omb1 = 1.0f - beta1,  omb2 = 1.0f - beta2        (binary32 subtraction)
+ *   per element i:
+ *     g = widen(g16[i])
+ *     m = beta1*m[i] + omb1*g
+ *     v = beta2*v[i] + (omb2*g)*g
+ *     d = sqrt(v)*inv_sqrt_bc2 + eps
+ *     p = p[i]*decay - step_size*(m/d)
+ *     m[i]=m, v[i]=v, p[i]=p, p_lp[i]=bf16_round_nearest_even(p)
+ */
+#ifndef DOS_H
+#define DOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dos_status {
+  DOS_OK = 0,
+  DOS_EINVAL = -1,  /* NULL pointer, bad hyper-parameter, bad size or count          */
+  DOS_EALIGN = -2,  /* an array is not 16-byte aligned                               */
+  DOS_EBUDGET = -3, /* GPU budget / staging memory too small for one slot            */
+  DOS_EHIP = -4,    /* a HIP call failed (sticky in a context)                       */
+  DOS_ESTATE = -5   /* memory location and requested target do not fit together      */
+} dos_status;
+
+typedef enum dos_loc { DOS_HOST_PINNED = 0, DOS_DEVICE = 1 } dos_loc;
+typedef enum dos_target { DOS_ON_CPU = 0, DOS_ON_GPU = 1 } dos_target;
+
+/* One subgroup of the flat optimizer partition (Section 2 "ZeRO": a rank's
+ * parameters are cut into subgroups; p16, g16, p32, m32, v32 are cut alike).
+ * All five arrays have n elements and are owned by the caller.  p, m, v live
+ * where state_loc says (pinned host memory or device memory), g where grad_loc
+ * says.  p_lp is device memory in dos_adam_step and dos_run_update_phase (it is
+ * a slice of the 16-bit model on the GPU) and host memory in
+ * dos_adam_step_host.  Every pointer must be 16-byte aligned. */
+typedef struct dos_subgroup {
+  float* p;          /* FP32 master parameters, in/out, updated in place  */
+  float* m;          /* FP32 first moment (momentum), in/out              */
+  float* v;          /* FP32 second moment (variance), in/out             */
+  const uint16_t* g; /* bf16 gradient bit patterns, in                    */
+  uint16_t* p_lp;    /* bf16 bit patterns of the updated parameters, out  */
+  uint64_t n;        /* elements; 0 is allowed and is a no-op             */
+  int32_t state_loc; /* dos_loc of p, m, v                                */
+  int32_t grad_loc;  /* dos_loc of g                                      */
+} dos_subgroup;
+
+/* AdamW hyper-parameters as binary32 values; step is 1-based and names the step
+ * being taken (it is not modified).  Valid: step >= 1, 0 <= beta < 1, eps >= 0,
+ * all values finite. */
+typedef struct dos_hparams {
+  float lr, beta1, beta2, eps, weight_decay;
+  int64_t step;
+} dos_hparams;
+
+/* Launch shape of the fused kernel, for tuning sweeps; all-zero = defaults. */
+typedef struct dos_launch_cfg {
+  int32_t variant;       /* kernel layout variant, see dos_adam_step_cfg          */
+  int32_t block_threads; /* 0 = default (256); multiple of 64, <= 1024            */
+  int32_t grid_blocks;   /* 0 = one tile per block; else grid-stride over tiles   */
+} dos_launch_cfg;
+
+/* ---- device-resident update (Algorithm 1, gpu_update) ---------------------
+ * Fused AdamW over one subgroup whose five arrays are all device memory.
+ * Asynchronous on hip_stream (a hipStream_t, NULL = the default stream); no
+ * allocation, no synchronisation.  HBM traffic is 28 bytes per element (reads
+ * 4+4+4+2, writes 4+4+4+2).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
+ * state_loc/grad_loc not DOS_DEVICE is DOS_ESTATE), DOS_EALIGN, DOS_EHIP. */
+dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);
+
+/* Same, with an explicit launch shape.  variant 0: each lane handles 4
+ * consecutive elements per trip (16-byte FP32 accesses, 8-byte bf16), two trips
+ * unrolled; variant 1: one trip; variant 2: four trips; variant 3: each lane
+ * handles 8 consecutive elements (two 16-byte FP32 accesses, 16-byte bf16).
+ * Negative or unknown values: DOS_EINVAL. */
+dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
+                             const dos_launch_cfg* cfg);
+
+/* ---- host update (Algorithm 1, cpu_update + the FP32->16-bit downscale, fused)
+ * The same arithmetic on host cores over host memory, bit-identical to the
+ * device kernel.  All five arrays are host pointers (p_lp too).  threads <= 0
+ * means one thread.  Synchronous. */
+dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hparams* hp, int32_t threads);
+
+/* ---- planner (Section 4.2 performance model, Section 4.3 Algorithm 1) ------ */
+
+/* Measured or assumed rates.  h2d/d2h in bytes per second (per direction, under
+ * duplex load), update rates in parameters per second.  downscale_params_per_s
+ * is the paper's D_c; 0 means the downscale is fused into the host update
+ * (1/D_c = 0). */
+typedef struct dos_cost_model {
+  double h2d_Bps, d2h_Bps;
+  double gpu_params_per_s, cpu_params_per_s;
+  double downscale_params_per_s;
+  double launch_overhead_s;
+} dos_cost_model;
+
+enum { DOS_PLAN_STRIDE = 0, DOS_PLAN_BALANCED = 1 };
+
+/* Output of the planner.  target, order and resident are caller-provided arrays
+ * of n_sg entries (resident may be NULL). */
+typedef struct dos_plan {
+  int32_t n_sg;
+  int32_t n_slots;       /* staging slots that fit the budget (capped)                 */
+  uint64_t slot_params;  /* capacity of one slot in parameters (<= largest subgroup)   */
+  uint8_t* target;       /* dos_target per subgroup                                    */
+  int32_t* order;        /* processing order: a permutation of 0..n_sg-1               */
+  uint8_t* resident;     /* 1 = keep p,m,v on the GPU across steps (static resident)   */
+  int32_t stride_k;      /* Eq. 1 rounded (stride mode), 0 = no dynamic GPU subgroup   */
+  double stride_k_real;  /* Eq. 1 before rounding                                      */
+  double predicted_s;    /* cost-model makespan of the plan                            */
+  double lower_bound_s;  /* max(H2D bytes / h2d_Bps, D2H bytes / d2h_Bps) of the plan  */
+} dos_plan;
+
+/* Pure, deterministic, host-only.
+ *   mode DOS_PLAN_STRIDE:   k = (3/B + 1/U_g) / (1/U_c + 1/D_c - 1/(2B)) with B in
+ *     parameters/s (h2d_Bps/4), rounded to nearest, at least 1; subgroup i goes
+ *     to the GPU when (i+1) % k == 0 (Eq. 1 and Algorithm 1).
+ *   mode DOS_PLAN_BALANCED: minimises this library's own makespan estimate
+ *     (dos_plan_cost) over the number and choice of GPU subgroups.
+ * gpu_budget_bytes is the device memory the phase may use for FP32 staging and
+ * static residents; bytes_per_param_slot is 12 (p, m, v) or 14 (gradients
+ * staged too).  Slots get the largest subgroup's size when at least two fit,
+ * otherwise a third of the budget (subgroups then stream through in pieces);
+ * fewer than 64 Ki parameters per slot is DOS_EBUDGET.  At most 4 slots are used.  With n_resident_max > 0
+ * the planner may mark up to that many trailing subgroups as static residents
+ * if they fit the budget next to the staging slots (Section 4.1: residents are
+ * placed last). */
+dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, int32_t n_sg,
+                              uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot, int32_t mode,
+                              int32_t n_resident_max, dos_plan* out);
+
+/* The makespan estimate the balanced mode minimises, for any assignment:
+ * predicted = max(host lane, GPU lane), lower = max(link time per direction). */
+dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* target,
+                         const uint8_t* resident, int32_t n_sg, int32_t n_slots,
+                         double* predicted_s, double* lower_bound_s);
+
+/* ---- interleaved update phase (Sections 4.1, 4.3) ------------------------- */
+
+typedef struct dos_ctx dos_ctx;
+
+enum { DOS_CTX_PROFILE = 1 }; /* time every copy and kernel with events */
+
+typedef struct dos_ctx_config {
+  void* slot_mem;          /* device memory for the staging ring (caller allocates)   */
+  uint64_t slot_bytes;     /* its size                                                */
+  uint64_t slot_params;    /* capacity of one slot in parameters                      */
+  int32_t n_slots;         /* slots to use; n_slots*14*slot_params <= slot_bytes      */
+  int32_t host_threads;    /* worker threads for CPU-planned subgroups (>= 1)         */
+  void* h2d_stream;        /* hipStream_t for prefetches, NULL = library creates one  */
+  void* compute_stream;    /* hipStream_t for kernels                                 */
+  void* d2h_stream;        /* hipStream_t for flushes                                 */
+  void* upload_stream;     /* hipStream_t for 16-bit parameter uploads                */
+  void* pinned_stage;      /* pinned host memory for the 16-bit upload ring           */
+  uint64_t pinned_stage_bytes;
+  uint64_t upload_chunk_params; /* 0 = default (4 Mi)                                 */
+  int32_t flags;
+  int32_t device;          /* HIP device ordinal                                      */
+} dos_ctx_config;
+
+typedef struct dos_phase_stats {
+  double wall_s;                  /* call entry to join                               */
+  double h2d_bytes, d2h_bytes;    /* bytes moved over the host link per direction     */
+  double h2d_busy_s, d2h_busy_s;  /* summed copy durations (DOS_CTX_PROFILE), else -1 */
+  double gpu_busy_s;              /* summed kernel durations (DOS_CTX_PROFILE)        */
+  double duplex_overlap_s;        /* time both directions were busy at once           */
+  double cpu_lane_s;              /* first host update start to last upload enqueued  */
+  double gpu_lane_s;              /* phase start to last flush landed                 */
+  uint64_t params_gpu, params_cpu, params_resident;
+  int32_t n_gpu, n_cpu, n_resident, n_slots;
+  int32_t n_pieces, host_threads;
+} dos_phase_stats;
+
+dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg);
+void dos_ctx_destroy(dos_ctx* ctx);
+
+/* One update phase over all subgroups (Algorithm 1 run_update, re-designed as
+ * two concurrent lanes).  GPU-planned subgroups in pinned host memory are
+ * prefetched into a staging slot (H2D stream), updated there (compute stream)
+ * and flushed back (D2H stream), slot by slot, piece by piece; static residents
+ * (state_loc == DOS_DEVICE) are updated in place, last; CPU-planned subgroups
+ * are updated by the host worker threads, which write the 16-bit parameters
+ * into the pinned upload ring and send them to p_lp on the upload stream.
+ * Synchronous at the boundary: on return every p, m, v is back where state_loc
+ * says and every p_lp has landed on the device.  plan->target / plan->order
+ * decide the placement and the order inside each lane.  Errors leave all state
+ * untouched when they are detected by validation (DOS_EINVAL, DOS_EALIGN,
+ * DOS_ESTATE, DOS_EBUDGET); DOS_EHIP is sticky and state is then undefined. */
+dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
+                                const dos_hparams* hp, dos_phase_stats* stats);
+
+/* Measures the rates of dos_cost_model on this machine with the context's own
+ * slots, streams and worker threads: pinned copies each way under duplex load,
+ * the device kernel over one slot, the host update over the upload ring. */
+dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
+
+/* ---- utilities ------------------------------------------------------------ */
+
+/* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */
+dos_status dos_pinned_alloc(void** out, uint64_t bytes);
+dos_status dos_pinned_free(void* ptr);
+
+const char* dos_strerror(dos_status s);
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char* dos_last_hip_error(void);
+int32_t dos_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DOS_H */

@@ -88,7 +88,7 @@ def run_update_trace(n_sg: int, k: int, residents: Iterable[int] = ()) -> List[T
 
 def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d2h_Bps: float,
                gpu_params_per_s: float, cpu_params_per_s: float, launch_overhead_s: float,
-               n_slots: int) -> Tuple[float, float]:
+               n_slots: int, resident: Sequence[int] = ()) -> Tuple[float, float]:
     """(predicted_s, lower_bound_s) of one update phase.
 
     CPU-planned subgroups cost n/U_c on the host and 2 bytes/param of H2D for the
@@ -96,19 +96,23 @@ def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d
     (p, m, v in FP32) and n/U_g + launch on the GPU.  With two or more staging
     slots the three lanes overlap and only the first prefetch and its kernel are
     exposed in front of the D2H lane; with a single slot prefetch, kernel and
-    flush of every GPU subgroup run back to back."""
+    flush of every GPU subgroup run back to back.  Static residents (indices in
+    ``resident``, all GPU-planned) never cross the link: they only add GPU time."""
     assert len(sizes) == len(target)
-    n_g = [n for n, t in zip(sizes, target) if t == ON_GPU]
+    R = set(resident)
+    assert all(target[i] == ON_GPU for i in R)
+    n_g = [n for i, (n, t) in enumerate(zip(sizes, target)) if t == ON_GPU and i not in R]
+    n_r = [sizes[i] for i in R]
     n_c = [n for n, t in zip(sizes, target) if t == ON_CPU]
-    N_G, N_C = float(sum(n_g)), float(sum(n_c))
+    N_G, N_C, N_R = float(sum(n_g)), float(sum(n_c)), float(sum(n_r))
     h2d_bytes = 12.0 * N_G + 2.0 * N_C
     d2h_bytes = 12.0 * N_G
     t_h2d = h2d_bytes / h2d_Bps
     t_d2h = d2h_bytes / d2h_Bps
     t_cpu = N_C / cpu_params_per_s
-    t_gpu = N_G / gpu_params_per_s + launch_overhead_s * len(n_g)
+    t_gpu = (N_G + N_R) / gpu_params_per_s + launch_overhead_s * (len(n_g) + len(n_r))
     if not n_g:
-        lane = t_h2d
+        lane = max(t_h2d, t_gpu)
     elif n_slots >= 2:
         first = n_g[0]
         lead = 12.0 * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s

@@ -1,0 +1,119 @@
+// Host side of the AdamW update: per-step scalars, argument checks, and the
+// host-core update used for CPU-planned subgroups (Algorithm 1, cpu_update, with
+// the FP32->16-bit downscale of Section 4.1 fused into the same pass).
+//
+// The host loop performs the same binary32 operations in the same order as the
+// device kernel; the file is built with -ffp-contract=off and without fast-math,
+// so the auto-vectorised code (IEEE divide and square root in every x86 vector
+// width) is bit-identical to the device result.
+#include <math.h>
+#include <string.h>
+
+#include <thread>
+#include <vector>
+
+#include "dos_internal.h"
+
+namespace dos {
+
+dos_status make_scalars(const dos_hparams* hp, AdamScalars* out) {
+  if (!hp || !out) return DOS_EINVAL;
+  const float lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, eps = hp->eps, wd = hp->weight_decay;
+  if (hp->step < 1) return DOS_EINVAL;
+  if (!isfinite(lr) || !isfinite(wd) || !isfinite(eps)) return DOS_EINVAL;
+  if (!(b1 >= 0.0f && b1 < 1.0f) || !(b2 >= 0.0f && b2 < 1.0f) || !(eps >= 0.0f)) return DOS_EINVAL;
+  const double t = (double)hp->step;
+  const double bc1 = 1.0 - pow((double)b1, t);
+  const double bc2 = 1.0 - pow((double)b2, t);
+  out->beta1 = b1;
+  out->beta2 = b2;
+  out->omb1 = 1.0f - b1;
+  out->omb2 = 1.0f - b2;
+  out->step_size = (float)((double)lr / bc1);
+  out->inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+  out->eps = eps;
+  out->decay = (float)(1.0 - (double)lr * (double)wd);
+  return DOS_OK;
+}
+
+dos_status check_subgroup_pointers(const dos_subgroup* sg) {
+  if (!sg) return DOS_EINVAL;
+  if (sg->n == 0) return DOS_OK;
+  if (!sg->p || !sg->m || !sg->v || !sg->g || !sg->p_lp) return DOS_EINVAL;
+  const uintptr_t bits = (uintptr_t)sg->p | (uintptr_t)sg->m | (uintptr_t)sg->v | (uintptr_t)sg->g |
+                         (uintptr_t)sg->p_lp;
+  if (bits & 15u) return DOS_EALIGN;
+  return DOS_OK;
+}
+
+namespace {
+
+inline uint16_t bf16_rne_host(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  const uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t q = (u >> 16) | 0x0040u;
+  return (uint16_t)(((u & 0x7FFFFFFFu) > 0x7F800000u) ? q : r);
+}
+
+// The loop the compiler vectorises.  Clones for wider vector units are picked at
+// load time; all of them perform the same IEEE operations.
+__attribute__((target_clones("avx512f", "avx2", "default")))
+void adam_block(float* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+                const uint16_t* __restrict__ g, uint16_t* __restrict__ p_lp, uint64_t n,
+                const AdamScalars s) {
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint32_t gb = (uint32_t)g[i] << 16;
+    float gi;
+    memcpy(&gi, &gb, 4);
+    const float mt = s.beta1 * m[i] + s.omb1 * gi;
+    const float vt = s.beta2 * v[i] + (s.omb2 * gi) * gi;
+    const float d = sqrtf(vt) * s.inv_sqrt_bc2 + s.eps;
+    const float pt = p[i] * s.decay - s.step_size * (mt / d);
+    m[i] = mt;
+    v[i] = vt;
+    p[i] = pt;
+    p_lp[i] = bf16_rne_host(pt);
+  }
+}
+
+}  // namespace
+
+void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
+                     const AdamScalars& s) {
+  adam_block(p, m, v, g, p_lp, n, s);
+}
+
+}  // namespace dos
+
+extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hparams* hp, int32_t threads) {
+  dos::AdamScalars s;
+  dos_status rc = dos::check_subgroup_pointers(sg);
+  if (rc != DOS_OK) return rc;
+  rc = dos::make_scalars(hp, &s);
+  if (rc != DOS_OK) return rc;
+  if (sg->n == 0) return DOS_OK;
+  if (sg->state_loc != DOS_HOST_PINNED || sg->grad_loc != DOS_HOST_PINNED) return DOS_ESTATE;
+  const uint64_t n = sg->n;
+  int T = threads < 1 ? 1 : threads;
+  const uint64_t min_per_thread = 1u << 16;
+  if ((uint64_t)T > (n + min_per_thread - 1) / min_per_thread) T = (int)((n + min_per_thread - 1) / min_per_thread);
+  if (T <= 1) {
+    dos::host_adam_range(sg->p, sg->m, sg->v, sg->g, sg->p_lp, n, s);
+    return DOS_OK;
+  }
+  // static split on 64-element boundaries
+  const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
+  std::vector<std::thread> pool;
+  pool.reserve(T);
+  for (int t = 0; t < T; ++t) {
+    const uint64_t lo = (uint64_t)t * per;
+    if (lo >= n) break;
+    const uint64_t cnt = (lo + per <= n) ? per : n - lo;
+    pool.emplace_back([=]() {
+      dos::host_adam_range(sg->p + lo, sg->m + lo, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
+    });
+  }
+  for (auto& th : pool) th.join();
+  return DOS_OK;
+}

@@ -1,0 +1,229 @@
+// Fused mixed-precision AdamW over one subgroup for gfx950 (MI355X).
+//
+// One pass over five arrays: FP32 p, m, v are read and rewritten in place, bf16
+// gradients are read and the bf16 copy of the new parameters is written --
+// 28 bytes of HBM traffic per element and nothing else (Section 4.1 of the
+// paper stages p, m, v and the gradient on the device, Algorithm 1 updates them
+// there and emits the 16-bit parameters; here the update and the downscale are
+// one kernel).  The kernel is bound by HBM bandwidth: ~0.5 flop per byte, no
+// reuse, so there is no LDS staging and no MFMA.  Every lane moves 16 bytes per
+// FP32 access; a wave's accesses are contiguous; a block owns a contiguous tile
+// so DRAM pages are opened once.
+//
+// Arithmetic: each operation is one IEEE binary32 operation (the file is built
+// with -ffp-contract=off, correctly rounded divide and square root, denormals
+// kept), in the order documented in dos.h.
+#include <hip/hip_runtime.h>
+
+#include "dos_internal.h"
+
+namespace dos {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* ptr) {
+  if constexpr (NT) return __builtin_nontemporal_load(ptr);
+  else return *ptr;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* ptr, T val) {
+  if constexpr (NT) __builtin_nontemporal_store(val, ptr);
+  else *ptr = val;
+}
+
+// binary32 -> bf16 bit pattern, round to nearest even; NaN kept as quiet NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x0040u) : r;
+}
+
+// One element; returns the bf16 bits of the new parameter.
+__device__ __forceinline__ uint32_t adam_element(const AdamScalars& s, float& p, float& m, float& v,
+                                                 uint32_t g_bits_hi) {
+  const float g = __uint_as_float(g_bits_hi);  // bf16 in the upper half: exact widening
+  const float mt = s.beta1 * m + s.omb1 * g;
+  const float vt = s.beta2 * v + (s.omb2 * g) * g;
+  const float d = __builtin_sqrtf(vt) * s.inv_sqrt_bc2 + s.eps;
+  const float pt = p * s.decay - s.step_size * (mt / d);
+  m = mt;
+  v = vt;
+  p = pt;
+  return bf16_rne(pt);
+}
+
+// Four consecutive elements held by one lane.
+__device__ __forceinline__ u32x2 adam_quad(const AdamScalars& s, f32x4& p, f32x4& m, f32x4& v, u32x2 g) {
+  float p0 = p.x, p1 = p.y, p2 = p.z, p3 = p.w;
+  float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
+  float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
+  const uint32_t b0 = adam_element(s, p0, m0, v0, g.x << 16);
+  const uint32_t b1 = adam_element(s, p1, m1, v1, g.x & 0xFFFF0000u);
+  const uint32_t b2 = adam_element(s, p2, m2, v2, g.y << 16);
+  const uint32_t b3 = adam_element(s, p3, m3, v3, g.y & 0xFFFF0000u);
+  p.x = p0; p.y = p1; p.z = p2; p.w = p3;
+  m.x = m0; m.y = m1; m.z = m2; m.w = m3;
+  v.x = v0; v.y = v1; v.z = v2; v.w = v3;
+  u32x2 out;
+  out.x = b0 | (b1 << 16);
+  out.y = b2 | (b3 << 16);
+  return out;
+}
+
+// Elements [4*n_quads, n): at most three, handled by the first lanes of block 0.
+__device__ __forceinline__ void adam_tail(float* p, float* m, float* v, const uint16_t* g,
+                                          uint16_t* p_lp, uint64_t n_quads, uint64_t n,
+                                          const AdamScalars& s) {
+  const uint64_t i = n_quads * 4 + threadIdx.x;
+  if (blockIdx.x == 0 && i < n) {
+    float pi = p[i], mi = m[i], vi = v[i];
+    const uint32_t b = adam_element(s, pi, mi, vi, (uint32_t)g[i] << 16);
+    p[i] = pi; m[i] = mi; v[i] = vi;
+    p_lp[i] = (uint16_t)b;
+  }
+}
+
+// Layout A: a lane handles 4 consecutive elements per trip, TRIPS trips per tile,
+// trips of one tile are blockDim.x*4 elements apart (every wave access is 1 KiB
+// contiguous for FP32, 512 B for bf16).
+template <int TRIPS, bool NTL, bool NTS>
+__global__ __launch_bounds__(512) void adam_kernel_quads(float* __restrict__ p, float* __restrict__ m,
+                                                         float* __restrict__ v,
+                                                         const uint16_t* __restrict__ g,
+                                                         uint16_t* __restrict__ p_lp, uint64_t n,
+                                                         AdamScalars s) {
+  const uint64_t n_quads = n >> 2;
+  const uint64_t tile = (uint64_t)blockDim.x * TRIPS;
+  const uint64_t n_tiles = (n_quads + tile - 1) / tile;
+  f32x4* __restrict__ p4 = reinterpret_cast<f32x4*>(p);
+  f32x4* __restrict__ m4 = reinterpret_cast<f32x4*>(m);
+  f32x4* __restrict__ v4 = reinterpret_cast<f32x4*>(v);
+  const u32x2* __restrict__ g4 = reinterpret_cast<const u32x2*>(g);
+  u32x2* __restrict__ o4 = reinterpret_cast<u32x2*>(p_lp);
+
+  for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const uint64_t base = t * tile + threadIdx.x;
+    f32x4 P[TRIPS], M[TRIPS], V[TRIPS];
+    u32x2 G[TRIPS];
+#pragma unroll
+    for (int k = 0; k < TRIPS; ++k) {
+      const uint64_t q = base + (uint64_t)k * blockDim.x;
+      if (q < n_quads) {
+        G[k] = ld<NTL>(g4 + q);
+        P[k] = ld<NTL>(p4 + q);
+        M[k] = ld<NTL>(m4 + q);
+        V[k] = ld<NTL>(v4 + q);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < TRIPS; ++k) {
+      const uint64_t q = base + (uint64_t)k * blockDim.x;
+      if (q < n_quads) {
+        const u32x2 o = adam_quad(s, P[k], M[k], V[k], G[k]);
+        st<NTS>(m4 + q, M[k]);
+        st<NTS>(v4 + q, V[k]);
+        st<NTS>(p4 + q, P[k]);
+        st<NTS>(o4 + q, o);
+      }
+    }
+  }
+  adam_tail(p, m, v, g, p_lp, n_quads, n, s);
+}
+
+// Layout B: a lane handles 8 consecutive elements per trip (two adjacent 16-byte
+// FP32 accesses, one 16-byte bf16 access).
+template <bool NTL, bool NTS>
+__global__ __launch_bounds__(512) void adam_kernel_octets(float* __restrict__ p, float* __restrict__ m,
+                                                          float* __restrict__ v,
+                                                          const uint16_t* __restrict__ g,
+                                                          uint16_t* __restrict__ p_lp, uint64_t n,
+                                                          AdamScalars s) {
+  const uint64_t n_oct = n >> 3;
+  f32x4* __restrict__ p4 = reinterpret_cast<f32x4*>(p);
+  f32x4* __restrict__ m4 = reinterpret_cast<f32x4*>(m);
+  f32x4* __restrict__ v4 = reinterpret_cast<f32x4*>(v);
+  const u32x4* __restrict__ g8 = reinterpret_cast<const u32x4*>(g);
+  u32x4* __restrict__ o8 = reinterpret_cast<u32x4*>(p_lp);
+  const uint64_t n_tiles = (n_oct + blockDim.x - 1) / blockDim.x;
+  for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const uint64_t q = t * blockDim.x + threadIdx.x;
+    if (q < n_oct) {
+      const u32x4 G = ld<NTL>(g8 + q);
+      f32x4 P0 = ld<NTL>(p4 + 2 * q), P1 = ld<NTL>(p4 + 2 * q + 1);
+      f32x4 M0 = ld<NTL>(m4 + 2 * q), M1 = ld<NTL>(m4 + 2 * q + 1);
+      f32x4 V0 = ld<NTL>(v4 + 2 * q), V1 = ld<NTL>(v4 + 2 * q + 1);
+      u32x2 ga, gb;
+      ga.x = G.x; ga.y = G.y; gb.x = G.z; gb.y = G.w;
+      const u32x2 oa = adam_quad(s, P0, M0, V0, ga);
+      const u32x2 ob = adam_quad(s, P1, M1, V1, gb);
+      u32x4 O;
+      O.x = oa.x; O.y = oa.y; O.z = ob.x; O.w = ob.y;
+      st<NTS>(m4 + 2 * q, M0); st<NTS>(m4 + 2 * q + 1, M1);
+      st<NTS>(v4 + 2 * q, V0); st<NTS>(v4 + 2 * q + 1, V1);
+      st<NTS>(p4 + 2 * q, P0); st<NTS>(p4 + 2 * q + 1, P1);
+      st<NTS>(o8 + q, O);
+    }
+  }
+  // elements [8*n_oct, n): at most seven, scalar, first lanes of block 0
+  const uint64_t i = n_oct * 8 + threadIdx.x;
+  if (blockIdx.x == 0 && i < n) {
+    float pi = p[i], mi = m[i], vi = v[i];
+    const uint32_t b = adam_element(s, pi, mi, vi, (uint32_t)g[i] << 16);
+    p[i] = pi; m[i] = mi; v[i] = vi;
+    p_lp[i] = (uint16_t)b;
+  }
+}
+
+template <bool NTL, bool NTS>
+dos_status launch_layout(int layout, dim3 grid, dim3 block, hipStream_t st_, float* p, float* m, float* v,
+                         const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s) {
+  switch (layout) {
+    case 0: hipLaunchKernelGGL((adam_kernel_quads<2, NTL, NTS>), grid, block, 0, st_, p, m, v, g, lp, n, s); break;
+    case 1: hipLaunchKernelGGL((adam_kernel_quads<1, NTL, NTS>), grid, block, 0, st_, p, m, v, g, lp, n, s); break;
+    case 2: hipLaunchKernelGGL((adam_kernel_quads<4, NTL, NTS>), grid, block, 0, st_, p, m, v, g, lp, n, s); break;
+    case 3: hipLaunchKernelGGL((adam_kernel_octets<NTL, NTS>), grid, block, 0, st_, p, m, v, g, lp, n, s); break;
+    default: return DOS_EINVAL;
+  }
+  return DOS_OK;
+}
+
+}  // namespace
+
+dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
+                       const AdamScalars& s, void* stream, const dos_launch_cfg* cfg) {
+  if (n == 0) return DOS_OK;
+  int variant = cfg ? cfg->variant : 0;
+  int threads = (cfg && cfg->block_threads) ? cfg->block_threads : 256;
+  int64_t blocks = cfg ? cfg->grid_blocks : 0;
+  if (variant < 0 || threads < 64 || threads > 512 || (threads % 64) != 0 || blocks < 0) return DOS_EINVAL;
+  const int layout = variant & 0xF;
+  const bool ntl = (variant & 0x10) != 0, nts = (variant & 0x20) != 0;
+  if (layout > 3 || (variant & ~0x3F)) return DOS_EINVAL;
+  static const int trips_of[4] = {2, 1, 4, 1};
+  const uint64_t units = (layout == 3) ? (n >> 3) : (n >> 2);
+  const uint64_t tile = (uint64_t)threads * trips_of[layout];
+  uint64_t n_tiles = (units + tile - 1) / tile;
+  if (n_tiles == 0) n_tiles = 1;  // tail only
+  if (blocks == 0 || (uint64_t)blocks > n_tiles) blocks = (int64_t)n_tiles;
+  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;  // grid-stride covers the rest
+  dim3 grid((unsigned)blocks), block((unsigned)threads);
+  hipStream_t st_ = reinterpret_cast<hipStream_t>(stream);
+  dos_status rc;
+  if (ntl && nts) rc = launch_layout<true, true>(layout, grid, block, st_, p, m, v, g, p_lp, n, s);
+  else if (ntl) rc = launch_layout<true, false>(layout, grid, block, st_, p, m, v, g, p_lp, n, s);
+  else if (nts) rc = launch_layout<false, true>(layout, grid, block, st_, p, m, v, g, p_lp, n, s);
+  else rc = launch_layout<false, false>(layout, grid, block, st_, p, m, v, g, p_lp, n, s);
+  if (rc != DOS_OK) return rc;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    note_hip_error((int)e, "launch of the fused AdamW kernel");
+    return DOS_EHIP;
+  }
+  return DOS_OK;
+}
+
+}  // namespace dos

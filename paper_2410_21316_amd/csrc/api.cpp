@@ -1,0 +1,78 @@
+// C-ABI entry points that need no context: the device-resident update, pinned
+// host memory, and error text.
+#include <hip/hip_runtime_api.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "dos_internal.h"
+
+namespace dos {
+
+static thread_local char g_hip_error[256] = "";
+
+void note_hip_error(int code, const char* what) {
+  snprintf(g_hip_error, sizeof g_hip_error, "%s: %s (%d)", what, hipGetErrorString((hipError_t)code), code);
+}
+
+}  // namespace dos
+
+extern "C" {
+
+dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
+                             const dos_launch_cfg* cfg) {
+  dos::AdamScalars s;
+  dos_status rc = dos::check_subgroup_pointers(sg);
+  if (rc != DOS_OK) return rc;
+  rc = dos::make_scalars(hp, &s);
+  if (rc != DOS_OK) return rc;
+  if (sg->n == 0) return DOS_OK;
+  if (sg->state_loc != DOS_DEVICE || sg->grad_loc != DOS_DEVICE) return DOS_ESTATE;
+  return dos::launch_adam(sg->p, sg->m, sg->v, sg->g, sg->p_lp, sg->n, s, hip_stream, cfg);
+}
+
+dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream) {
+  return dos_adam_step_cfg(sg, hp, hip_stream, nullptr);
+}
+
+dos_status dos_pinned_alloc(void** out, uint64_t bytes) {
+  if (!out || bytes == 0) return DOS_EINVAL;
+  *out = nullptr;
+  void* ptr = nullptr;
+  hipError_t e = hipHostMalloc(&ptr, (size_t)bytes, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    dos::note_hip_error((int)e, "hipHostMalloc");
+    (void)hipGetLastError();
+    return DOS_EHIP;
+  }
+  *out = ptr;
+  return DOS_OK;
+}
+
+dos_status dos_pinned_free(void* ptr) {
+  if (!ptr) return DOS_OK;
+  hipError_t e = hipHostFree(ptr);
+  if (e != hipSuccess) {
+    dos::note_hip_error((int)e, "hipHostFree");
+    (void)hipGetLastError();
+    return DOS_EHIP;
+  }
+  return DOS_OK;
+}
+
+const char* dos_strerror(dos_status s) {
+  switch (s) {
+    case DOS_OK: return "ok";
+    case DOS_EINVAL: return "invalid argument";
+    case DOS_EALIGN: return "array not 16-byte aligned";
+    case DOS_EBUDGET: return "GPU budget or staging memory too small";
+    case DOS_EHIP: return "HIP call failed";
+    case DOS_ESTATE: return "memory location does not fit the requested target";
+  }
+  return "unknown status";
+}
+
+const char* dos_last_hip_error(void) { return dos::g_hip_error; }
+
+int32_t dos_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Internal declarations shared by the translation units of libdos.
+#pragma once
+
+#include <stdint.h>
+
+#include "dos.h"
+
+namespace dos {
+
+// The eight binary32 scalars of one step, derived once on the host
+// (formed in double, each rounded to binary32 once).
+struct AdamScalars {
+  float beta1, beta2, omb1, omb2, step_size, inv_sqrt_bc2, eps, decay;
+};
+
+// Validates the hyper-parameters and derives the scalars.
+dos_status make_scalars(const dos_hparams* hp, AdamScalars* out);
+
+// True when every pointer of the subgroup is non-NULL (or n == 0) and 16-byte aligned.
+dos_status check_subgroup_pointers(const dos_subgroup* sg);
+
+// Enqueues the fused kernel over n elements on `stream`.  Pointers are device
+// memory, 16-byte aligned (checked by the callers).  Returns DOS_EHIP when the
+// launch fails, DOS_EINVAL for an unknown launch shape.
+dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
+                       const AdamScalars& s, void* stream, const dos_launch_cfg* cfg);
+
+// Host update of elements [0, n) on the calling thread (vectorised, bit-identical
+// to the device kernel).
+void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
+                     const AdamScalars& s);
+
+// Records the text of a failed HIP call for dos_last_hip_error().
+void note_hip_error(int code, const char* what);
+
+}  // namespace dos

@@ -1,0 +1,629 @@
+// The interleaved update phase (Sections 4.1 and 4.3 of the paper), re-designed
+// for one MI355X and its host cores as two concurrent lanes:
+//
+//   GPU lane   -- every GPU-planned subgroup that lives in pinned host memory is
+//                 cut into pieces of at most one staging slot; piece j uses slot
+//                 j mod n_slots:  H2D stream: wait(slot free), copy p, m, v (and
+//                 g when it is host-resident) in, record(ready);  compute stream:
+//                 wait(ready), fused AdamW kernel, record(done);  D2H stream:
+//                 wait(done), copy p, m, v back, record(free).  Everything is
+//                 enqueued up front; the three streams and their events form the
+//                 pipeline, prefetch and flush run full duplex.  Static residents
+//                 (state already in device memory) are updated in place, last.
+//   host lane  -- persistent worker threads take chunks of the CPU-planned
+//                 subgroups, run the host AdamW (which writes the 16-bit
+//                 parameters straight into a pinned ring: the paper's separate
+//                 downscale pass is fused away) and send each chunk to the
+//                 device model on a fourth stream.
+//
+// The call joins both lanes before it returns.  Nothing is allocated here: slots,
+// ring, streams, events and threads belong to the context.
+#include <hip/hip_runtime_api.h>
+#include <string.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "dos_internal.h"
+
+namespace {
+
+using clk = std::chrono::steady_clock;
+inline double secs(clk::time_point a, clk::time_point b) {
+  return std::chrono::duration<double>(b - a).count();
+}
+
+constexpr int kMaxSlots = 16;
+constexpr int kProfPieces = 4096;  // pieces per phase that can be timed individually
+
+struct Chunk {  // a piece of a CPU-planned subgroup
+  int sg;
+  uint64_t off, cnt;
+};
+
+struct Piece {  // a piece of a GPU-planned, host-resident subgroup
+  int sg;
+  uint64_t off, cnt;
+};
+
+}  // namespace
+
+struct dos_ctx {
+  int device = 0;
+  int flags = 0;
+  hipStream_t h2d = nullptr, comp = nullptr, d2h = nullptr, upl = nullptr;
+  bool own_h2d = false, own_comp = false, own_d2h = false, own_upl = false;
+  // staging ring on the device
+  char* slot_mem = nullptr;
+  uint64_t slot_params = 0, slot_stride = 0;
+  int n_slots = 0;
+  bool slots_hold_grads = false;
+  hipEvent_t ready[kMaxSlots] = {}, done[kMaxSlots] = {}, freed[kMaxSlots] = {};
+  // 16-bit upload ring in pinned host memory
+  char* stage = nullptr;
+  uint64_t chunk_params = 0;
+  int ring_n = 0;
+  std::vector<hipEvent_t> ring_ev;
+  std::vector<std::atomic<int64_t>> ring_seq;  // last chunk index recorded on each ring entry
+  // profiling events
+  std::vector<hipEvent_t> prof;  // 6 per piece
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  // host workers
+  int T = 1;
+  std::vector<std::thread> workers;
+  std::mutex mu;
+  std::condition_variable cv_start, cv_done;
+  uint64_t generation = 0;
+  int running = 0;
+  bool quit = false;
+  // the job the workers see
+  const dos_subgroup* job_sgs = nullptr;
+  const std::vector<Chunk>* job_chunks = nullptr;
+  dos::AdamScalars job_scalars{};
+  std::atomic<int64_t> next_chunk{0};
+  std::atomic<int> job_error{0};
+  std::mutex upl_mu;
+  clk::time_point cpu_first, cpu_last;
+  std::atomic<bool> cpu_started{false};
+  // scratch lists reused across phases (reserved at creation)
+  std::vector<Chunk> chunks;
+  std::vector<Piece> pieces;
+  dos_status sticky = DOS_OK;
+};
+
+namespace {
+
+#define HIP_TRY(ctx, call, what)                \
+  do {                                          \
+    hipError_t e_ = (call);                     \
+    if (e_ != hipSuccess) {                     \
+      dos::note_hip_error((int)e_, what);       \
+      (void)hipGetLastError();                  \
+      (ctx)->sticky = DOS_EHIP;                 \
+      return DOS_EHIP;                          \
+    }                                           \
+  } while (0)
+
+void worker_main(dos_ctx* c, int /*tid*/) {
+  (void)hipSetDevice(c->device);
+  uint64_t seen = 0;
+  for (;;) {
+    {
+      std::unique_lock<std::mutex> lk(c->mu);
+      c->cv_start.wait(lk, [&] { return c->quit || c->generation != seen; });
+      if (c->quit) return;
+      seen = c->generation;
+    }
+    const std::vector<Chunk>& chunks = *c->job_chunks;
+    const int64_t total = (int64_t)chunks.size();
+    for (;;) {
+      const int64_t ci = c->next_chunk.fetch_add(1);
+      if (ci >= total || c->job_error.load()) break;
+      if (!c->cpu_started.exchange(true)) c->cpu_first = clk::now();
+      const Chunk& ch = chunks[ci];
+      const dos_subgroup& sg = c->job_sgs[ch.sg];
+      const int r = (int)(ci % c->ring_n);
+      // the ring entry is free once the upload of chunk ci - ring_n has landed
+      if (ci >= c->ring_n) {
+        while (c->ring_seq[r].load(std::memory_order_acquire) != ci - c->ring_n) {
+          if (c->job_error.load()) break;
+          std::this_thread::yield();
+        }
+        if (c->job_error.load()) break;
+        if (hipEventSynchronize(c->ring_ev[r]) != hipSuccess) {
+          c->job_error.store(1);
+          break;
+        }
+      }
+      uint16_t* out = reinterpret_cast<uint16_t*>(c->stage + (uint64_t)r * c->chunk_params * 2);
+      dos::host_adam_range(sg.p + ch.off, sg.m + ch.off, sg.v + ch.off, sg.g + ch.off, out, ch.cnt,
+                           c->job_scalars);
+      {
+        std::lock_guard<std::mutex> lk(c->upl_mu);
+        hipError_t e = hipMemcpyAsync(sg.p_lp + ch.off, out, ch.cnt * 2, hipMemcpyHostToDevice, c->upl);
+        if (e == hipSuccess) e = hipEventRecord(c->ring_ev[r], c->upl);
+        if (e != hipSuccess) {
+          dos::note_hip_error((int)e, "upload of 16-bit parameters");
+          c->job_error.store(1);
+        }
+      }
+      c->ring_seq[r].store(ci, std::memory_order_release);
+    }
+    {
+      std::lock_guard<std::mutex> lk(c->mu);
+      c->cpu_last = clk::now();
+      if (--c->running == 0) c->cv_done.notify_all();
+    }
+  }
+}
+
+void destroy(dos_ctx* c) {
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->quit = true;
+  }
+  c->cv_start.notify_all();
+  for (auto& t : c->workers) t.join();
+  (void)hipSetDevice(c->device);
+  for (int s = 0; s < kMaxSlots; ++s) {
+    if (c->ready[s]) (void)hipEventDestroy(c->ready[s]);
+    if (c->done[s]) (void)hipEventDestroy(c->done[s]);
+    if (c->freed[s]) (void)hipEventDestroy(c->freed[s]);
+  }
+  for (auto e : c->ring_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto e : c->prof)
+    if (e) (void)hipEventDestroy(e);
+  if (c->t0) (void)hipEventDestroy(c->t0);
+  if (c->t1) (void)hipEventDestroy(c->t1);
+  if (c->own_h2d && c->h2d) (void)hipStreamDestroy(c->h2d);
+  if (c->own_comp && c->comp) (void)hipStreamDestroy(c->comp);
+  if (c->own_d2h && c->d2h) (void)hipStreamDestroy(c->d2h);
+  if (c->own_upl && c->upl) (void)hipStreamDestroy(c->upl);
+  delete c;
+}
+
+// Length of the union of [a,b) intervals intersected with the union of another set.
+double overlap_of_unions(std::vector<std::pair<double, double>> a, std::vector<std::pair<double, double>> b) {
+  auto merge = [](std::vector<std::pair<double, double>>& v) {
+    std::sort(v.begin(), v.end());
+    std::vector<std::pair<double, double>> out;
+    for (auto& iv : v) {
+      if (!out.empty() && iv.first <= out.back().second) out.back().second = std::max(out.back().second, iv.second);
+      else out.push_back(iv);
+    }
+    v.swap(out);
+  };
+  merge(a);
+  merge(b);
+  double tot = 0;
+  size_t i = 0, j = 0;
+  while (i < a.size() && j < b.size()) {
+    const double lo = std::max(a[i].first, b[j].first), hi = std::min(a[i].second, b[j].second);
+    if (hi > lo) tot += hi - lo;
+    if (a[i].second < b[j].second) ++i; else ++j;
+  }
+  return tot;
+}
+
+}  // namespace
+
+extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
+  if (!out) return DOS_EINVAL;
+  *out = nullptr;
+  if (!cfg || cfg->host_threads < 1 || cfg->host_threads > 1024 || cfg->n_slots < 0 || cfg->n_slots > kMaxSlots)
+    return DOS_EINVAL;
+  if (cfg->n_slots > 0) {
+    if (!cfg->slot_mem || cfg->slot_params == 0 || (cfg->slot_params & 63)) return DOS_EINVAL;
+    if ((uintptr_t)cfg->slot_mem & 255) return DOS_EALIGN;
+    if (cfg->slot_bytes / (uint64_t)cfg->n_slots / 12 < cfg->slot_params) return DOS_EBUDGET;
+  }
+  const uint64_t chunk = cfg->upload_chunk_params ? cfg->upload_chunk_params : (4u << 20);
+  if (chunk & 63) return DOS_EINVAL;
+  int ring_n = 0;
+  if (cfg->pinned_stage) {
+    if ((uintptr_t)cfg->pinned_stage & 255) return DOS_EALIGN;
+    ring_n = (int)std::min<uint64_t>(cfg->pinned_stage_bytes / (chunk * 2), 4096);
+    if (ring_n < 2) return DOS_EBUDGET;
+  }
+  if (hipSetDevice(cfg->device) != hipSuccess) {
+    (void)hipGetLastError();
+    return DOS_EHIP;
+  }
+  dos_ctx* c = new dos_ctx();
+  c->device = cfg->device;
+  c->flags = cfg->flags;
+  c->T = cfg->host_threads;
+  c->slot_mem = (char*)cfg->slot_mem;
+  c->slot_params = cfg->slot_params;
+  c->n_slots = cfg->n_slots;
+  if (c->n_slots > 0) {
+    const uint64_t per = cfg->slot_bytes / (uint64_t)c->n_slots;
+    c->slots_hold_grads = per / 14 >= c->slot_params;
+    c->slot_stride = (c->slots_hold_grads ? 14 : 12) * c->slot_params;
+  }
+  c->stage = (char*)cfg->pinned_stage;
+  c->chunk_params = chunk;
+  c->ring_n = ring_n;
+
+  auto fail = [&](hipError_t e, const char* what) {
+    dos::note_hip_error((int)e, what);
+    (void)hipGetLastError();
+    destroy(c);
+    return DOS_EHIP;
+  };
+  hipError_t e;
+  struct { void* given; hipStream_t* dst; bool* own; } st[4] = {
+      {cfg->h2d_stream, &c->h2d, &c->own_h2d}, {cfg->compute_stream, &c->comp, &c->own_comp},
+      {cfg->d2h_stream, &c->d2h, &c->own_d2h}, {cfg->upload_stream, &c->upl, &c->own_upl}};
+  for (auto& s : st) {
+    if (s.given) {
+      *s.dst = (hipStream_t)s.given;
+    } else {
+      if ((e = hipStreamCreateWithFlags(s.dst, hipStreamNonBlocking)) != hipSuccess) return fail(e, "hipStreamCreate");
+      *s.own = true;
+    }
+  }
+  for (int s = 0; s < c->n_slots; ++s) {
+    if ((e = hipEventCreateWithFlags(&c->ready[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    if ((e = hipEventCreateWithFlags(&c->done[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    if ((e = hipEventCreateWithFlags(&c->freed[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+  }
+  c->ring_ev.assign(ring_n, nullptr);
+  c->ring_seq = std::vector<std::atomic<int64_t>>(ring_n);
+  for (int r = 0; r < ring_n; ++r)
+    if ((e = hipEventCreateWithFlags(&c->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+  if ((e = hipEventCreate(&c->t0)) != hipSuccess) return fail(e, "hipEventCreate");
+  if ((e = hipEventCreate(&c->t1)) != hipSuccess) return fail(e, "hipEventCreate");
+  if (c->flags & DOS_CTX_PROFILE) {
+    c->prof.assign((size_t)kProfPieces * 6, nullptr);
+    for (auto& ev : c->prof)
+      if ((e = hipEventCreate(&ev)) != hipSuccess) return fail(e, "hipEventCreate");
+  }
+  c->chunks.reserve(1 << 16);
+  c->pieces.reserve(1 << 14);
+  c->workers.reserve(c->T);
+  for (int t = 0; t < c->T; ++t) c->workers.emplace_back(worker_main, c, t);
+  *out = c;
+  return DOS_OK;
+}
+
+extern "C" void dos_ctx_destroy(dos_ctx* ctx) {
+  if (ctx) destroy(ctx);
+}
+
+extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
+                                           const dos_hparams* hp, dos_phase_stats* stats) {
+  const auto t_entry = clk::now();
+  if (!c || !plan || n_sg < 0 || (n_sg > 0 && (!sgs || !plan->target || !plan->order))) return DOS_EINVAL;
+  if (c->sticky != DOS_OK) return c->sticky;
+  if (plan->n_sg != n_sg) return DOS_EINVAL;
+  dos::AdamScalars sc;
+  dos_status rc = dos::make_scalars(hp, &sc);
+  if (rc != DOS_OK) return rc;
+
+  // ---- validation: nothing is touched before every subgroup has been checked
+  std::vector<Chunk>& chunks = c->chunks;
+  std::vector<Piece>& pieces = c->pieces;
+  chunks.clear();
+  pieces.clear();
+  {
+    // order must be a permutation
+    uint64_t seen_words[(1 << 16) / 64] = {};
+    if (n_sg > (1 << 16)) return DOS_EINVAL;
+    for (int k = 0; k < n_sg; ++k) {
+      const int i = plan->order[k];
+      if (i < 0 || i >= n_sg || (seen_words[i >> 6] >> (i & 63) & 1)) return DOS_EINVAL;
+      seen_words[i >> 6] |= (uint64_t)1 << (i & 63);
+    }
+  }
+  uint64_t params_gpu = 0, params_cpu = 0, params_res = 0;
+  int n_gpu = 0, n_cpu = 0, n_res = 0;
+  for (int k = 0; k < n_sg; ++k) {
+    const int i = plan->order[k];
+    const dos_subgroup& sg = sgs[i];
+    if ((rc = dos::check_subgroup_pointers(&sg)) != DOS_OK) return rc;
+    if (plan->target[i] > DOS_ON_GPU) return DOS_EINVAL;
+    if (sg.state_loc != DOS_HOST_PINNED && sg.state_loc != DOS_DEVICE) return DOS_EINVAL;
+    if (sg.grad_loc != DOS_HOST_PINNED && sg.grad_loc != DOS_DEVICE) return DOS_EINVAL;
+    if (sg.n == 0) continue;
+    if (plan->target[i] == DOS_ON_CPU) {
+      if (sg.state_loc != DOS_HOST_PINNED || sg.grad_loc != DOS_HOST_PINNED) return DOS_ESTATE;
+      if (c->ring_n < 2) return DOS_EBUDGET;
+      for (uint64_t off = 0; off < sg.n; off += c->chunk_params)
+        chunks.push_back({i, off, std::min(c->chunk_params, sg.n - off)});
+      params_cpu += sg.n;
+      ++n_cpu;
+    } else if (sg.state_loc == DOS_DEVICE) {  // static resident
+      if (sg.grad_loc != DOS_DEVICE) return DOS_ESTATE;
+      params_res += sg.n;
+      ++n_res;
+    } else {
+      if (c->n_slots < 1) return DOS_EBUDGET;
+      if (sg.grad_loc == DOS_HOST_PINNED && !c->slots_hold_grads) return DOS_EBUDGET;
+      for (uint64_t off = 0; off < sg.n; off += c->slot_params)
+        pieces.push_back({i, off, std::min(c->slot_params, sg.n - off)});
+      params_gpu += sg.n;
+      ++n_gpu;
+    }
+  }
+
+  HIP_TRY(c, hipSetDevice(c->device), "hipSetDevice");
+  const bool prof = (c->flags & DOS_CTX_PROFILE) && pieces.size() <= (size_t)kProfPieces;
+
+  // ---- host lane: wake the workers
+  if (!chunks.empty()) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->job_sgs = sgs;
+    c->job_chunks = &chunks;
+    c->job_scalars = sc;
+    c->next_chunk.store(0);
+    c->job_error.store(0);
+    c->cpu_started.store(false);
+    for (int r = 0; r < c->ring_n; ++r) c->ring_seq[r].store(-1);
+    c->running = c->T;
+    ++c->generation;
+  }
+  if (!chunks.empty()) c->cv_start.notify_all();
+
+  // ---- GPU lane: enqueue every piece
+  dos_status gpu_rc = DOS_OK;
+  auto enqueue_gpu = [&]() -> dos_status {
+    HIP_TRY(c, hipEventRecord(c->t0, c->h2d), "hipEventRecord");
+    // the other streams start no earlier than t0 (keeps the timeline comparable)
+    for (size_t j = 0; j < pieces.size(); ++j) {
+      const Piece& pc = pieces[j];
+      const dos_subgroup& sg = sgs[pc.sg];
+      const int s = (int)(j % (size_t)c->n_slots);
+      char* base = c->slot_mem + (uint64_t)s * c->slot_stride;
+      float* sp = (float*)base;
+      float* sm = (float*)(base + 4 * c->slot_params);
+      float* sv = (float*)(base + 8 * c->slot_params);
+      uint16_t* sgd = (uint16_t*)(base + 12 * c->slot_params);
+      const size_t fb = pc.cnt * 4;
+      hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
+      if (j >= (size_t)c->n_slots) HIP_TRY(c, hipStreamWaitEvent(c->h2d, c->freed[s], 0), "hipStreamWaitEvent");
+      if (pe) HIP_TRY(c, hipEventRecord(pe[0], c->h2d), "hipEventRecord");
+      HIP_TRY(c, hipMemcpyAsync(sp, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of p");
+      HIP_TRY(c, hipMemcpyAsync(sm, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of m");
+      HIP_TRY(c, hipMemcpyAsync(sv, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of v");
+      const uint16_t* gdev = sg.g + pc.off;
+      if (sg.grad_loc == DOS_HOST_PINNED) {
+        HIP_TRY(c, hipMemcpyAsync(sgd, sg.g + pc.off, pc.cnt * 2, hipMemcpyHostToDevice, c->h2d), "prefetch of g");
+        gdev = sgd;
+      }
+      if (pe) HIP_TRY(c, hipEventRecord(pe[1], c->h2d), "hipEventRecord");
+      HIP_TRY(c, hipEventRecord(c->ready[s], c->h2d), "hipEventRecord");
+
+      HIP_TRY(c, hipStreamWaitEvent(c->comp, c->ready[s], 0), "hipStreamWaitEvent");
+      if (pe) HIP_TRY(c, hipEventRecord(pe[2], c->comp), "hipEventRecord");
+      dos_status k = dos::launch_adam(sp, sm, sv, gdev, sg.p_lp + pc.off, pc.cnt, sc, c->comp, nullptr);
+      if (k != DOS_OK) {
+        c->sticky = k;
+        return k;
+      }
+      if (pe) HIP_TRY(c, hipEventRecord(pe[3], c->comp), "hipEventRecord");
+      HIP_TRY(c, hipEventRecord(c->done[s], c->comp), "hipEventRecord");
+
+      HIP_TRY(c, hipStreamWaitEvent(c->d2h, c->done[s], 0), "hipStreamWaitEvent");
+      if (pe) HIP_TRY(c, hipEventRecord(pe[4], c->d2h), "hipEventRecord");
+      HIP_TRY(c, hipMemcpyAsync(sg.p + pc.off, sp, fb, hipMemcpyDeviceToHost, c->d2h), "flush of p");
+      HIP_TRY(c, hipMemcpyAsync(sg.m + pc.off, sm, fb, hipMemcpyDeviceToHost, c->d2h), "flush of m");
+      HIP_TRY(c, hipMemcpyAsync(sg.v + pc.off, sv, fb, hipMemcpyDeviceToHost, c->d2h), "flush of v");
+      if (pe) HIP_TRY(c, hipEventRecord(pe[5], c->d2h), "hipEventRecord");
+      HIP_TRY(c, hipEventRecord(c->freed[s], c->d2h), "hipEventRecord");
+    }
+    // static residents, placed last: their kernels overlap the tail transfers
+    for (int k = 0; k < n_sg; ++k) {
+      const int i = plan->order[k];
+      const dos_subgroup& sg = sgs[i];
+      if (sg.n == 0 || plan->target[i] != DOS_ON_GPU || sg.state_loc != DOS_DEVICE) continue;
+      dos_status kr = dos::launch_adam(sg.p, sg.m, sg.v, sg.g, sg.p_lp, sg.n, sc, c->comp, nullptr);
+      if (kr != DOS_OK) {
+        c->sticky = kr;
+        return kr;
+      }
+    }
+    return DOS_OK;
+  };
+  gpu_rc = enqueue_gpu();
+
+  // ---- join: host lane first (it keeps enqueueing uploads), then the streams
+  if (!chunks.empty()) {
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv_done.wait(lk, [&] { return c->running == 0; });
+  }
+  hipError_t e1 = hipStreamSynchronize(c->h2d);
+  hipError_t e2 = hipStreamSynchronize(c->comp);
+  hipError_t e3 = hipStreamSynchronize(c->d2h);
+  const auto t_gpu_done = clk::now();
+  hipError_t e4 = hipStreamSynchronize(c->upl);
+  const auto t_exit = clk::now();
+  if (gpu_rc != DOS_OK) return gpu_rc;
+  for (hipError_t e : {e1, e2, e3, e4})
+    if (e != hipSuccess) {
+      dos::note_hip_error((int)e, "hipStreamSynchronize at the end of the update phase");
+      (void)hipGetLastError();
+      c->sticky = DOS_EHIP;
+      return DOS_EHIP;
+    }
+  if (c->job_error.load()) {
+    c->sticky = DOS_EHIP;
+    return DOS_EHIP;
+  }
+
+  if (stats) {
+    memset(stats, 0, sizeof *stats);
+    stats->wall_s = secs(t_entry, t_exit);
+    stats->h2d_bytes = 12.0 * (double)params_gpu + 2.0 * (double)params_cpu;
+    for (const Piece& pc : pieces)
+      if (sgs[pc.sg].grad_loc == DOS_HOST_PINNED) stats->h2d_bytes += 2.0 * (double)pc.cnt;
+    stats->d2h_bytes = 12.0 * (double)params_gpu;
+    stats->h2d_busy_s = stats->d2h_busy_s = stats->gpu_busy_s = stats->duplex_overlap_s = -1.0;
+    stats->cpu_lane_s = chunks.empty() ? 0.0 : secs(c->cpu_first, c->cpu_last);
+    stats->gpu_lane_s = secs(t_entry, t_gpu_done);
+    stats->params_gpu = params_gpu;
+    stats->params_cpu = params_cpu;
+    stats->params_resident = params_res;
+    stats->n_gpu = n_gpu;
+    stats->n_cpu = n_cpu;
+    stats->n_resident = n_res;
+    stats->n_slots = c->n_slots;
+    stats->n_pieces = (int32_t)pieces.size();
+    stats->host_threads = c->T;
+    if (prof && !pieces.empty()) {
+      std::vector<std::pair<double, double>> up, down;
+      double hb = 0, db = 0, gb = 0;
+      bool ok = true;
+      for (size_t j = 0; j < pieces.size() && ok; ++j) {
+        hipEvent_t* pe = &c->prof[j * 6];
+        float t[6];
+        for (int q = 0; q < 6; ++q)
+          if (hipEventElapsedTime(&t[q], c->t0, pe[q]) != hipSuccess) {
+            (void)hipGetLastError();
+            ok = false;
+          }
+        if (!ok) break;
+        hb += (t[1] - t[0]) * 1e-3;
+        gb += (t[3] - t[2]) * 1e-3;
+        db += (t[5] - t[4]) * 1e-3;
+        up.emplace_back(t[0] * 1e-3, t[1] * 1e-3);
+        down.emplace_back(t[4] * 1e-3, t[5] * 1e-3);
+      }
+      if (ok) {
+        stats->h2d_busy_s = hb;
+        stats->d2h_busy_s = db;
+        stats->gpu_busy_s = gb;
+        stats->duplex_overlap_s = overlap_of_unions(up, down);
+      }
+    }
+  }
+  return DOS_OK;
+}
+
+// Rates of the cost model measured with the context's own resources.
+extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
+  if (!c || !out) return DOS_EINVAL;
+  if (c->sticky != DOS_OK) return c->sticky;
+  if (c->n_slots < 1 || c->ring_n < 2) return DOS_EBUDGET;
+  HIP_TRY(c, hipSetDevice(c->device), "hipSetDevice");
+  memset(out, 0, sizeof *out);
+  const uint64_t stage_bytes = (uint64_t)c->ring_n * c->chunk_params * 2;
+  const uint64_t half = (stage_bytes / 2) & ~(uint64_t)255;
+  const uint64_t slot_bytes = c->slot_stride;
+  // the device side of both copies sits in slot 0 (first and second half)
+  const uint64_t nbytes = std::min<uint64_t>(half, (slot_bytes / 2) & ~(uint64_t)255);
+  if (nbytes < (1u << 20)) return DOS_EBUDGET;
+  char* dev_a = c->slot_mem;
+  char* dev_b = c->slot_mem + nbytes;
+  char* host_a = c->stage;
+  char* host_b = c->stage + half;
+  memset(c->stage, 0, stage_bytes);
+  HIP_TRY(c, hipMemsetAsync(c->slot_mem, 0, slot_bytes, c->comp), "hipMemsetAsync");
+  HIP_TRY(c, hipStreamSynchronize(c->comp), "hipStreamSynchronize");
+
+  hipEvent_t ev[4];
+  for (auto& e : ev) HIP_TRY(c, hipEventCreate(&e), "hipEventCreate");
+  auto cleanup = [&] { for (auto& e : ev) (void)hipEventDestroy(e); };
+  const int reps = (int)std::max<uint64_t>(2, std::min<uint64_t>(64, ((uint64_t)2 << 30) / nbytes));
+  // warm-up, then both directions at once
+  for (int pass = 0; pass < 2; ++pass) {
+    hipError_t e = hipEventRecord(ev[0], c->h2d);
+    if (e == hipSuccess) e = hipEventRecord(ev[2], c->d2h);
+    for (int r = 0; r < (pass ? reps : 1) && e == hipSuccess; ++r) {
+      e = hipMemcpyAsync(dev_a, host_a, nbytes, hipMemcpyHostToDevice, c->h2d);
+      if (e == hipSuccess) e = hipMemcpyAsync(host_b, dev_b, nbytes, hipMemcpyDeviceToHost, c->d2h);
+    }
+    if (e == hipSuccess) e = hipEventRecord(ev[1], c->h2d);
+    if (e == hipSuccess) e = hipEventRecord(ev[3], c->d2h);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->d2h);
+    if (e != hipSuccess) {
+      cleanup();
+      HIP_TRY(c, e, "calibration copies");
+    }
+  }
+  float ms_up = 0, ms_down = 0;
+  hipError_t e = hipEventElapsedTime(&ms_up, ev[0], ev[1]);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms_down, ev[2], ev[3]);
+  if (e != hipSuccess) {
+    cleanup();
+    HIP_TRY(c, e, "hipEventElapsedTime");
+  }
+  out->h2d_Bps = (double)nbytes * reps / (ms_up * 1e-3);
+  out->d2h_Bps = (double)nbytes * reps / (ms_down * 1e-3);
+
+  // device kernel over slot 0: five arrays carved out of the slot
+  {
+    const uint64_t n = (slot_bytes / 28) & ~(uint64_t)63;
+    float* p = (float*)c->slot_mem;
+    float* m = p + n;
+    float* v = m + n;
+    uint16_t* g = (uint16_t*)(v + n);
+    uint16_t* lp = g + n;
+    dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f};
+    const int kreps = 5;
+    dos_status k = dos::launch_adam(p, m, v, g, lp, n, sc, c->comp, nullptr);  // warm-up
+    hipError_t he = hipEventRecord(ev[0], c->comp);
+    for (int r = 0; r < kreps && k == DOS_OK; ++r) k = dos::launch_adam(p, m, v, g, lp, n, sc, c->comp, nullptr);
+    if (he == hipSuccess) he = hipEventRecord(ev[1], c->comp);
+    if (he == hipSuccess) he = hipStreamSynchronize(c->comp);
+    float ms = 0;
+    if (he == hipSuccess) he = hipEventElapsedTime(&ms, ev[0], ev[1]);
+    if (k != DOS_OK || he != hipSuccess) {
+      cleanup();
+      if (k != DOS_OK) return k;
+      HIP_TRY(c, he, "calibration kernel");
+    }
+    out->gpu_params_per_s = (double)n * kreps / (ms * 1e-3);
+    // launch overhead: the same kernel over 64 elements
+    he = hipEventRecord(ev[0], c->comp);
+    for (int r = 0; r < 20 && k == DOS_OK; ++r) k = dos::launch_adam(p, m, v, g, lp, 64, sc, c->comp, nullptr);
+    if (he == hipSuccess) he = hipEventRecord(ev[1], c->comp);
+    if (he == hipSuccess) he = hipStreamSynchronize(c->comp);
+    if (he == hipSuccess) he = hipEventElapsedTime(&ms, ev[0], ev[1]);
+    if (k != DOS_OK || he != hipSuccess) {
+      cleanup();
+      if (k != DOS_OK) return k;
+      HIP_TRY(c, he, "calibration kernel");
+    }
+    out->launch_overhead_s = ms * 1e-3 / 20;
+  }
+  cleanup();
+
+  // host update over the pinned ring with all worker threads (the ring is small
+  // next to a real subgroup, so this is an upper estimate when it fits in cache)
+  {
+    const uint64_t n = (stage_bytes / 28) & ~(uint64_t)63;
+    float* p = (float*)c->stage;
+    float* m = p + n;
+    float* v = m + n;
+    uint16_t* g = (uint16_t*)(v + n);
+    uint16_t* lp = g + n;
+    dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f};
+    const int T = c->T;
+    const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
+    auto run = [&] {
+      std::vector<std::thread> th;
+      for (int t = 0; t < T; ++t) {
+        const uint64_t lo = (uint64_t)t * per;
+        if (lo >= n) break;
+        const uint64_t cnt = std::min(per, n - lo);
+        th.emplace_back([=] { dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc); });
+      }
+      for (auto& t : th) t.join();
+    };
+    run();
+    const auto a = clk::now();
+    const int hreps = 3;
+    for (int r = 0; r < hreps; ++r) run();
+    out->cpu_params_per_s = (double)n * hreps / secs(a, clk::now());
+  }
+  out->downscale_params_per_s = 0.0;
+  return DOS_OK;
+}

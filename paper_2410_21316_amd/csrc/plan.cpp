@@ -1,0 +1,206 @@
+// CPU/GPU subgroup planner: the performance model of Section 4.2 (Eq. 1), the
+// stride placement of Algorithm 1 (Section 4.3), and a "balanced" mode that
+// minimises this library's own makespan estimate for unequal subgroup sizes,
+// per-direction link rates and a fused host downscale.  Pure host code.
+#include <math.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "dos_internal.h"
+
+namespace {
+
+constexpr int kMaxSlots = 4;
+constexpr uint64_t kMinSlotParams = 1u << 16;
+
+struct Cost {
+  double predicted, lower;
+};
+
+bool valid_cost_model(const dos_cost_model* cm) {
+  return cm && cm->h2d_Bps > 0 && cm->d2h_Bps > 0 && cm->gpu_params_per_s > 0 &&
+         cm->cpu_params_per_s > 0 && cm->downscale_params_per_s >= 0 && cm->launch_overhead_s >= 0 &&
+         isfinite(cm->h2d_Bps) && isfinite(cm->d2h_Bps) && isfinite(cm->gpu_params_per_s) &&
+         isfinite(cm->cpu_params_per_s) && isfinite(cm->downscale_params_per_s) &&
+         isfinite(cm->launch_overhead_s);
+}
+
+// Makespan estimate of one phase.  CPU-planned subgroups: n/U_c on the host and
+// 2 B/param of H2D.  Dynamic GPU subgroups: 12 B/param each way plus n/U_g and a
+// launch.  Residents: GPU time only.  With >= 2 slots the lanes overlap and only
+// the first prefetch + kernel lead the D2H lane; with one slot they serialise.
+Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* target,
+              const uint8_t* resident, int n, int n_slots) {
+  double NG = 0, NC = 0, NR = 0, first = -1;
+  int cg = 0, cr = 0;
+  for (int i = 0; i < n; ++i) {
+    const double s = (double)sizes[i];
+    if (target[i] == DOS_ON_CPU) {
+      NC += s;
+    } else if (resident && resident[i]) {
+      NR += s;
+      ++cr;
+    } else {
+      if (first < 0) first = s;
+      NG += s;
+      ++cg;
+    }
+  }
+  const double h2d_bytes = 12.0 * NG + 2.0 * NC, d2h_bytes = 12.0 * NG;
+  const double t_h2d = h2d_bytes / cm.h2d_Bps, t_d2h = d2h_bytes / cm.d2h_Bps;
+  const double t_cpu = NC / cm.cpu_params_per_s;
+  const double t_gpu = (NG + NR) / cm.gpu_params_per_s + cm.launch_overhead_s * (cg + cr);
+  double lane;
+  if (cg == 0) {
+    lane = std::max(t_h2d, t_gpu);
+  } else if (n_slots >= 2) {
+    const double lead = 12.0 * first / cm.h2d_Bps + first / cm.gpu_params_per_s + cm.launch_overhead_s;
+    lane = std::max(std::max(t_h2d, lead + t_d2h), t_gpu);
+  } else {
+    lane = std::max(12.0 * NG / cm.h2d_Bps + t_gpu + t_d2h, t_h2d);
+  }
+  return {std::max(t_cpu, lane), std::max(t_h2d, t_d2h)};
+}
+
+}  // namespace
+
+extern "C" dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* target,
+                                    const uint8_t* resident, int32_t n_sg, int32_t n_slots,
+                                    double* predicted_s, double* lower_bound_s) {
+  if (!valid_cost_model(cm) || n_sg < 0 || n_slots < 1 || !predicted_s || !lower_bound_s) return DOS_EINVAL;
+  if (n_sg > 0 && (!sizes || !target)) return DOS_EINVAL;
+  for (int i = 0; i < n_sg; ++i) {
+    if (target[i] > DOS_ON_GPU) return DOS_EINVAL;
+    if (resident && resident[i] && target[i] != DOS_ON_GPU) return DOS_ESTATE;
+  }
+  const Cost c = evaluate(*cm, sizes, target, resident, n_sg, n_slots);
+  *predicted_s = c.predicted;
+  *lower_bound_s = c.lower;
+  return DOS_OK;
+}
+
+extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, int32_t n_sg,
+                                         uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
+                                         int32_t mode, int32_t n_resident_max, dos_plan* out) {
+  if (!valid_cost_model(cm) || !out || n_sg < 0 || n_resident_max < 0) return DOS_EINVAL;
+  if (mode != DOS_PLAN_STRIDE && mode != DOS_PLAN_BALANCED) return DOS_EINVAL;
+  if (bytes_per_param_slot != 12 && bytes_per_param_slot != 14) return DOS_EINVAL;
+  if (n_sg > 0 && (!sizes || !out->target || !out->order)) return DOS_EINVAL;
+  if (n_resident_max > 0 && !out->resident) return DOS_EINVAL;
+  uint64_t s_max = 0;
+  for (int i = 0; i < n_sg; ++i) s_max = std::max(s_max, sizes[i]);
+
+  // ---- staging slots from the budget
+  const uint64_t bpp = (uint64_t)bytes_per_param_slot;
+  uint64_t slot_params;
+  int n_slots;
+  const uint64_t s_pad = (s_max + 63) & ~(uint64_t)63;  // keeps every slot array 16-byte aligned
+  if (s_pad > 0 && gpu_budget_bytes / bpp / 2 >= s_pad) {
+    slot_params = s_pad;
+    n_slots = (int)std::min<uint64_t>(kMaxSlots, gpu_budget_bytes / (bpp * s_pad));
+  } else {
+    slot_params = (gpu_budget_bytes / (3 * bpp)) & ~(uint64_t)0xFFFF;  // multiple of 64 Ki
+    n_slots = 3;
+    if (s_pad > 0 && slot_params > s_pad) {  // one whole subgroup fits, two do not
+      slot_params = s_pad;
+      n_slots = 1;
+    }
+  }
+  if (n_sg > 0 && slot_params < kMinSlotParams) return DOS_EBUDGET;
+
+  std::vector<uint8_t> target(n_sg, DOS_ON_CPU), resident(n_sg, 0);
+
+  // ---- static residents: trailing subgroups that fit next to the slots
+  uint64_t left = gpu_budget_bytes - std::min<uint64_t>(gpu_budget_bytes, (uint64_t)n_slots * bpp * slot_params);
+  int n_res = 0;
+  for (int i = n_sg - 1; i >= 0 && n_res < n_resident_max; --i) {
+    const uint64_t need = 12 * sizes[i];
+    if (need > left) break;
+    left -= need;
+    resident[i] = 1;
+    target[i] = DOS_ON_GPU;
+    ++n_res;
+  }
+  const int n_dyn = n_sg - n_res;
+
+  // ---- Eq. 1 (reported in both modes)
+  const double B = cm->h2d_Bps / 4.0;  // link rate in FP32 parameters per second
+  const double inv_dc = cm->downscale_params_per_s > 0 ? 1.0 / cm->downscale_params_per_s : 0.0;
+  const double den = 1.0 / cm->cpu_params_per_s + inv_dc - 1.0 / (2.0 * B);
+  double k_real = 0.0;
+  int k = 0;
+  if (den > 0.0) {
+    k_real = (3.0 / B + 1.0 / cm->gpu_params_per_s) / den;
+    k = std::max(1, (int)(k_real + 0.5));
+  }
+
+  auto cost_of = [&](const std::vector<uint8_t>& t) {
+    return evaluate(*cm, sizes, t.data(), resident.data(), n_sg, n_slots);
+  };
+
+  if (mode == DOS_PLAN_STRIDE) {
+    for (int i = 0; i < n_dyn; ++i)
+      if (k >= 1 && (i + 1) % k == 0) target[i] = DOS_ON_GPU;
+  } else {
+    // evenly spread c GPU subgroups among the dynamic ones (for c = n/k this is
+    // Algorithm 1's stride pattern), pick the best count ...
+    std::vector<uint8_t> best = target, cand = target;
+    double best_cost = cost_of(best).predicted;
+    for (int c = 1; c <= n_dyn; ++c) {
+      for (int i = 0; i < n_dyn; ++i)
+        cand[i] = ((int64_t)(i + 1) * c / n_dyn > (int64_t)i * c / n_dyn) ? DOS_ON_GPU : DOS_ON_CPU;
+      const double cc = cost_of(cand).predicted;
+      if (cc < best_cost) {
+        best_cost = cc;
+        best = cand;
+      }
+    }
+    // ... then improve by single moves and pair swaps while the estimate drops
+    // (unequal sizes make the best subset differ from the even spread).
+    bool improved = true;
+    for (int pass = 0; improved && pass < 64; ++pass) {
+      improved = false;
+      for (int i = 0; i < n_dyn; ++i) {
+        best[i] ^= 1;
+        const double cc = cost_of(best).predicted;
+        if (cc < best_cost * (1.0 - 1e-12)) {
+          best_cost = cc;
+          improved = true;
+        } else {
+          best[i] ^= 1;
+        }
+      }
+      if (n_dyn <= 96) {
+        for (int i = 0; i < n_dyn; ++i)
+          for (int j = i + 1; j < n_dyn; ++j) {
+            if (best[i] == best[j] || sizes[i] == sizes[j]) continue;
+            std::swap(best[i], best[j]);
+            const double cc = cost_of(best).predicted;
+            if (cc < best_cost * (1.0 - 1e-12)) {
+              best_cost = cc;
+              improved = true;
+            } else {
+              std::swap(best[i], best[j]);
+            }
+          }
+      }
+    }
+    target = best;
+  }
+
+  const Cost c = cost_of(target);
+  out->n_sg = n_sg;
+  out->n_slots = n_slots;
+  out->slot_params = slot_params;
+  out->stride_k = k;
+  out->stride_k_real = k_real;
+  out->predicted_s = c.predicted;
+  out->lower_bound_s = c.lower;
+  for (int i = 0; i < n_sg; ++i) {
+    out->target[i] = target[i];
+    out->order[i] = i;
+    if (out->resident) out->resident[i] = resident[i];
+  }
+  return DOS_OK;
+}

@@ -16,3 +16,5 @@ def pytest_configure(config):
 def hp():
     """AdamW hyper-parameters every workload in the configuration list uses."""
     return dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+sys.path.insert(0, os.path.join(ROOT, "tests"))

@@ -1,0 +1,85 @@
+"""The library's host-core update (CPU-planned subgroups) against the oracle: it
+must be bit-identical, for every thread count and on ragged sizes."""
+import numpy as np
+import pytest
+import torch
+
+import dos_synth as S
+import paper_2410_21316_amd as dos
+from oracle import adamw_oracle as ref
+
+
+def aligned(n, dtype):
+    raw = np.zeros(n * np.dtype(dtype).itemsize + 64, np.uint8)
+    off = (-raw.ctypes.data) % 64
+    return raw[off:off + n * np.dtype(dtype).itemsize].view(dtype)
+
+
+def make_state(n, seed, sg_index=0, **gkw):
+    p = aligned(n, np.float32); m = aligned(n, np.float32); v = aligned(n, np.float32)
+    g = aligned(n, np.uint16); lp = aligned(n, np.uint16)
+    p[:] = S.params(seed, sg_index, 0, n).numpy()
+    return p, m, v, g, lp
+
+
+def set_grads(g, seed, step, sg_index=0, **gkw):
+    g[:] = S.bits16(S.grads_bf16(seed, step, sg_index, 0, g.shape[0], **gkw)).numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("n,threads", [(1, 1), (63, 1), (4097, 1), (100_003, 1), (300_001, 4), (1 << 20, 8)])
+def test_host_update_is_bit_identical_to_oracle(n, threads, hp):
+    seed = S.BASE_SEED + n
+    mine = make_state(n, seed)
+    theirs = [x.copy() for x in mine]
+    for step in range(1, 5):
+        set_grads(mine[3], seed, step, zero_pct=1.0)
+        theirs[3][:] = mine[3]
+        sg = dos.subgroup(*(a.ctypes.data for a in mine), n, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+        dos.dos_adam_step_host(sg, dos.hparams(step=step, **hp), threads)
+        ref.adamw_step(*theirs, step=step, threads=0, **hp)
+        for a, b, name in zip(mine, theirs, "p m v g p_lp".split()):
+            assert a.tobytes() == b.tobytes(), (name, step)
+
+
+def test_host_update_heavy_tail_and_extreme_values(hp):
+    """Heavy-tailed gradients with exact zeros, plus hand-placed extremes: values
+    whose square underflows, huge gradients, denormal state, infinities, NaN."""
+    n = 50_000
+    seed = S.BASE_SEED + 77
+    mine = make_state(n, seed)
+    set_grads(mine[3], seed, 1, heavy_tail=True, zero_pct=5.0, scale=10.0)
+    p, m, v, g, lp = mine
+    bf = lambda x: ref.f32_to_bf16(np.array(x, np.float32))
+    g[:8] = bf([1e-30, -1e-25, 3e38, -3e38, 0.0, -0.0, np.inf, np.nan])
+    v[8:12] = np.array([1e-45, 1e-40, 0.0, 1e30], np.float32)
+    m[8:12] = np.array([1e-45, -1e-40, 1e-38, 1e20], np.float32)
+    p[12:16] = np.array([1e-45, -1e-38, 3e38, -0.0], np.float32)
+    theirs = [x.copy() for x in mine]
+    for step in (1, 2, 3):
+        sg = dos.subgroup(*(a.ctypes.data for a in mine), n, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+        dos.dos_adam_step_host(sg, dos.hparams(step=step, **hp), 3)
+        ref.adamw_step(*theirs, step=step, **hp)
+        for a, b, name in zip(mine, theirs, "p m v g p_lp".split()):
+            assert a.tobytes() == b.tobytes(), (name, step)
+    assert np.isnan(mine[0][7]) and np.isnan(mine[0][6])
+
+
+def test_host_update_empty_subgroup_is_a_noop(hp):
+    sg = dos.subgroup(None, None, None, None, None, 0, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+    dos.dos_adam_step_host(sg, dos.hparams(step=1, **hp), 4)
+
+
+def test_generator_is_deterministic_and_addressable():
+    a = S.grads_bf16(S.BASE_SEED, 3, 2, 0, 10_000, zero_pct=1.0)
+    b = S.grads_bf16(S.BASE_SEED, 3, 2, 2_000, 500, zero_pct=1.0)
+    assert torch.equal(a[2_000:2_500], b)
+    assert not torch.equal(a, S.grads_bf16(S.BASE_SEED, 4, 2, 0, 10_000, zero_pct=1.0))
+    assert not torch.equal(a, S.grads_bf16(S.BASE_SEED, 3, 1, 0, 10_000, zero_pct=1.0))
+    z = S.std_normal(S.stream_key(S.BASE_SEED, 0, 0, 0), 0, 1 << 18)
+    assert abs(float(z.mean())) < 0.01 and abs(float(z.std()) - 1.0) < 0.01
+    p = S.params(S.BASE_SEED, 0, 0, 1 << 16)
+    assert abs(float(p.std()) - 0.02) < 1e-3
+    zeros = float((S.grads_bf16(S.BASE_SEED, 1, 0, 0, 1 << 18, zero_pct=5.0, heavy_tail=True) == 0).float().mean())
+    assert abs(zeros - 0.05) < 0.005
+    s = [S.subgroup_scale(S.BASE_SEED, i) for i in range(200)]
+    assert 0.1 <= min(s) and max(s) <= 10.0 and min(s) < 0.3 and max(s) > 3.0
