@@ -1,0 +1,156 @@
+"""The interleaved update phase (dos_run_update_phase through the C ABI) must be
+bit-identical to running every subgroup through the oracle, for every plan,
+slot count, piece size and order."""
+import ctypes as C
+import random
+
+import numpy as np
+import pytest
+import torch
+
+import dos_synth as S
+import paper_2410_21316_amd as dos
+
+from gpu_util import OffloadedState, make_context
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [300_001, 262_144, 100_000, 65, 0, 500_003, 1_000_000, 64, 131_073]
+
+
+def run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=3, resident=None,
+                   grad_on_device=None, host_threads=4, chunk_params=1 << 16, ring_chunks=6, flags=0,
+                   seed=S.BASE_SEED, **gkw):
+    st = OffloadedState(sizes, seed, resident=resident, grad_on_device=grad_on_device, **gkw)
+    ctx = make_context(n_slots, slot_params, host_threads, chunk_params, ring_chunks, flags=flags)
+    plan = dos.Plan.manual(targets, order, n_slots, slot_params, resident)
+    stats = None
+    try:
+        for step in range(1, steps + 1):
+            st.set_grads(step)
+            stats = ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, **hp))
+            st.oracle_step(hp, step)
+            st.check(f"step {step} targets {targets} slots {n_slots}x{slot_params}")
+    finally:
+        ctx.close()
+        st.free()
+    return stats
+
+
+def test_alternate_subgroups_on_gpu_like_stride_two(hp):
+    """k = 2: every alternate subgroup on the GPU (Sections 5.3, 5.4)."""
+    targets = [(i + 1) % 2 == 0 for i in range(len(SIZES))]
+    stats = run_phase_case(SIZES, targets, None, 2, 1 << 20, hp, zero_pct=1.0)
+    n_g = sum(n for n, t in zip(SIZES, targets) if t)
+    n_c = sum(n for n, t in zip(SIZES, targets) if not t)
+    assert stats.params_gpu == n_g and stats.params_cpu == n_c
+    assert stats.d2h_bytes == 12.0 * n_g
+    assert stats.h2d_bytes == 12.0 * n_g + 2.0 * n_c + 2.0 * n_g     # gradients staged too here
+    assert stats.n_gpu == sum(1 for n, t in zip(SIZES, targets) if t and n)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_plans_slots_pieces_and_orders(case, hp):
+    rng = random.Random(1000 + case)
+    sizes = SIZES[:]
+    rng.shuffle(sizes)
+    targets = [rng.random() < 0.5 for _ in sizes]
+    order = list(range(len(sizes)))
+    rng.shuffle(order)
+    n_slots = rng.choice([1, 2, 3, 4])
+    slot_params = rng.choice([1 << 16, 3 << 16, 1 << 20])       # smaller than some subgroups: pieces
+    grad_dev = [t and rng.random() < 0.5 for t in targets]
+    run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=2, grad_on_device=grad_dev,
+                   host_threads=rng.choice([1, 3, 8]), chunk_params=rng.choice([1 << 12, 1 << 16]),
+                   ring_chunks=rng.choice([2, 3, 9]), seed=S.BASE_SEED + case, zero_pct=5.0, heavy_tail=True)
+
+
+def test_all_gpu_and_all_cpu_plans(hp):
+    run_phase_case(SIZES, [1] * len(SIZES), None, 3, 1 << 18, hp, steps=2)
+    run_phase_case(SIZES, [0] * len(SIZES), None, 0, 1 << 18, hp, steps=2)
+
+
+def test_static_residents_placed_last_update_in_place(hp):
+    """Update figure of Section 4.1: residents are the trailing subgroups; their
+    state never crosses the link."""
+    sizes = [200_000, 150_001, 300_000, 120_000, 250_007, 99_999, 180_000, 210_000]
+    resident = [0, 0, 0, 0, 0, 0, 1, 1]
+    targets = [0, 0, 1, 0, 0, 1, 1, 1]          # stride 3 plus the two residents
+    stats = run_phase_case(sizes, targets, None, 2, 1 << 18, hp, resident=resident,
+                           grad_on_device=[0, 0, 1, 0, 0, 1, 1, 1], flags=dos.DOS_CTX_PROFILE)
+    assert stats.n_resident == 2 and stats.params_resident == 390_000
+    assert stats.d2h_bytes == 12.0 * (300_000 + 99_999)
+    assert stats.h2d_bytes == 12.0 * (300_000 + 99_999) + 2.0 * (200_000 + 150_001 + 120_000 + 250_007)
+    assert stats.h2d_busy_s > 0 and stats.d2h_busy_s > 0 and stats.gpu_busy_s > 0
+
+
+def test_placement_does_not_change_results(hp):
+    """Subgroups update independently: any placement gives the same bits
+    (Section 4.1: out-of-order updates do not affect the result)."""
+    sizes = [100_000, 70_001, 130_000, 65_536]
+    results = []
+    for targets in ([0, 0, 0, 0], [1, 1, 1, 1], [1, 0, 1, 0], [0, 1, 0, 1]):
+        st = OffloadedState(sizes, S.BASE_SEED + 3)
+        ctx = make_context(2, 1 << 16)
+        plan = dos.Plan.manual(targets, None, 2, 1 << 16)
+        for step in (1, 2):
+            st.set_grads(step)
+            ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, **hp))
+        results.append(st.snapshot())
+        ctx.close(); st.free()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            for x, y in zip(a, b):
+                assert x.tobytes() == y.tobytes()
+
+
+def test_validation_errors_leave_state_untouched(hp):
+    sizes = [100_000, 50_000]
+    st = OffloadedState(sizes, S.BASE_SEED, grad_on_device=[1, 0])
+    st.set_grads(1)
+    ctx = make_context(2, 1 << 16, stage_grads=False)
+    lib = dos.load()
+    before = st.snapshot()
+    arr = (dos.dos_subgroup * 2)(*st.sgs)
+    stats = dos.dos_phase_stats()
+    good = dos.hparams(step=1, **hp)
+
+    def call(plan, hp_=good, n=2):
+        return lib.dos_run_update_phase(ctx._h, arr, n, C.byref(plan.c), C.byref(hp_), C.byref(stats))
+
+    assert call(dos.Plan.manual([1, 0])) == dos.DOS_OK                       # the valid call
+    st.oracle_step(hp, 1); st.check("valid call")
+    before = st.snapshot()
+    assert call(dos.Plan.manual([0, 0])) == dos.DOS_ESTATE                   # CPU plan, device grads
+    assert call(dos.Plan.manual([1, 1])) == dos.DOS_EBUDGET                  # host grads, 12-byte slots
+    assert call(dos.Plan.manual([1, 0], order=[0, 0])) == dos.DOS_EINVAL     # not a permutation
+    assert call(dos.Plan.manual([1, 0]), dos.hparams(step=0, **hp)) == dos.DOS_EINVAL
+    assert call(dos.Plan.manual([1, 0, 0]), n=2) == dos.DOS_EINVAL           # plan length mismatch
+    assert call(dos.Plan.manual([2, 0])) == dos.DOS_EINVAL
+    arr[1].p += 4
+    assert call(dos.Plan.manual([1, 0])) == dos.DOS_EALIGN
+    arr[1].p -= 4
+    for a, b in zip(before, st.snapshot()):
+        for x, y in zip(a, b):
+            assert x.tobytes() == y.tobytes()
+    ctx.close(); st.free()
+
+
+def test_transfers_overlap_full_duplex(hp):
+    """Prefetch of the next subgroup and flush of the previous one run at the
+    same time (Section 4.1); measured with the context's profiling events."""
+    sizes = [4_000_000] * 6
+    stats = run_phase_case(sizes, [1] * 6, None, 3, 4_000_000, hp, steps=1, grad_on_device=[1] * 6,
+                           flags=dos.DOS_CTX_PROFILE)
+    assert stats.duplex_overlap_s > 0.0
+    assert stats.n_pieces == 6
+
+
+def test_calibration_reports_plausible_rates():
+    ctx = make_context(2, 4 << 20, host_threads=8, chunk_params=1 << 20, ring_chunks=16)
+    cm = ctx.dos_calibrate()
+    ctx.close()
+    assert 5e9 < cm.h2d_Bps < 130e9 and 5e9 < cm.d2h_Bps < 130e9
+    assert 20e9 < cm.gpu_params_per_s < 400e9
+    assert 0.05e9 < cm.cpu_params_per_s < 100e9
+    assert 0 < cm.launch_overhead_s < 1e-3
