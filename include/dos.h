@@ -141,12 +141,16 @@ typedef struct dos_plan {
  *     parameters/s (h2d_Bps/4), rounded to nearest, at least 1; subgroup i goes
  *     to the GPU when (i+1) % k == 0 (Eq. 1 and Algorithm 1).
  *   mode DOS_PLAN_BALANCED: minimises this library's own makespan estimate
- *     (dos_plan_cost) over the number and choice of GPU subgroups.
+ *     (dos_plan_cost) over the number and choice of GPU subgroups: exhaustively
+ *     for up to 16 non-resident subgroups, otherwise an even spread of the best
+ *     count (Algorithm 1's stride pattern for n/k) improved by single moves and
+ *     pair swaps.
  * gpu_budget_bytes is the device memory the phase may use for FP32 staging and
  * static residents; bytes_per_param_slot is 12 (p, m, v) or 14 (gradients
- * staged too).  Slots get the largest subgroup's size when at least two fit,
- * otherwise a third of the budget (subgroups then stream through in pieces);
- * fewer than 64 Ki parameters per slot is DOS_EBUDGET.  At most 4 slots are used.  With n_resident_max > 0
+ * staged too).  Subgroups stream through the slots in pieces: a slot holds
+ * min(largest subgroup, 16 Mi) parameters when at least two such slots fit the
+ * budget, otherwise a third of the budget; at most 3 slots are used; fewer than
+ * 64 Ki parameters per slot is DOS_EBUDGET.  With n_resident_max > 0
  * the planner may mark up to that many trailing subgroups as static residents
  * if they fit the budget next to the staging slots (Section 4.1: residents are
  * placed last). */
@@ -155,16 +159,23 @@ dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, i
                               int32_t n_resident_max, dos_plan* out);
 
 /* The makespan estimate the balanced mode minimises, for any assignment:
- * predicted = max(host lane, GPU lane), lower = max(link time per direction). */
+ * predicted = max(host lane, GPU lane), lower = max(link time per direction).
+ * slot_params = 0 means whole subgroups are staged. */
 dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* target,
-                         const uint8_t* resident, int32_t n_sg, int32_t n_slots,
+                         const uint8_t* resident, int32_t n_sg, int32_t n_slots, uint64_t slot_params,
                          double* predicted_s, double* lower_bound_s);
 
 /* ---- interleaved update phase (Sections 4.1, 4.3) ------------------------- */
 
 typedef struct dos_ctx dos_ctx;
 
-enum { DOS_CTX_PROFILE = 1 }; /* time every copy and kernel with events */
+enum {
+  DOS_CTX_PROFILE = 1,    /* time every copy and kernel with events                            */
+  DOS_CTX_UPLOAD_DMA = 2, /* send 16-bit uploads with hipMemcpyAsync instead of the default
+                             pull-copy kernel (DMA uploads queue behind the bulk prefetches)  */
+  DOS_CTX_SPIN_WAIT = 4   /* the calling thread spins while it waits for a free slot instead
+                             of sleeping (takes a core from the host workers)                 */
+};
 
 typedef struct dos_ctx_config {
   void* slot_mem;          /* device memory for the staging ring (caller allocates)   */
@@ -191,6 +202,9 @@ typedef struct dos_phase_stats {
   double duplex_overlap_s;        /* time both directions were busy at once           */
   double cpu_lane_s;              /* first host update start to last upload enqueued  */
   double gpu_lane_s;              /* phase start to last flush landed                 */
+  double cpu_compute_s;           /* host update time, summed over worker threads     */
+  double cpu_wait_s;              /* waiting for a free upload-ring entry, summed     */
+  double cpu_enqueue_s;           /* enqueueing uploads, summed over worker threads   */
   uint64_t params_gpu, params_cpu, params_resident;
   int32_t n_gpu, n_cpu, n_resident, n_slots;
   int32_t n_pieces, host_threads;
@@ -224,6 +238,11 @@ dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 /* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */
 dos_status dos_pinned_alloc(void** out, uint64_t bytes);
 dos_status dos_pinned_free(void* ptr);
+
+/* Reads one byte of every 4 KiB page of a host buffer with `threads` threads, so
+ * that the first host update of a buffer that so far was only written by DMA does
+ * not pay for the page faults inside the update phase. */
+dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads);
 
 const char* dos_strerror(dos_status s);
 /* Text of the last HIP error seen by the calling thread ("" if none). */

@@ -88,14 +88,15 @@ def run_update_trace(n_sg: int, k: int, residents: Iterable[int] = ()) -> List[T
 
 def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d2h_Bps: float,
                gpu_params_per_s: float, cpu_params_per_s: float, launch_overhead_s: float,
-               n_slots: int, resident: Sequence[int] = ()) -> Tuple[float, float]:
+               n_slots: int, resident: Sequence[int] = (), slot_params: int = 0) -> Tuple[float, float]:
     """(predicted_s, lower_bound_s) of one update phase.
 
     CPU-planned subgroups cost n/U_c on the host and 2 bytes/param of H2D for the
     refreshed 16-bit parameters; GPU-planned ones cost 12 bytes/param each way
     (p, m, v in FP32) and n/U_g + launch on the GPU.  With two or more staging
     slots the three lanes overlap and only the first prefetch and its kernel are
-    exposed in front of the D2H lane; with a single slot prefetch, kernel and
+    exposed in front of the D2H lane (the first piece, when subgroups are staged in
+    pieces of ``slot_params``); with a single slot prefetch, kernel and
     flush of every GPU subgroup run back to back.  Static residents (indices in
     ``resident``, all GPU-planned) never cross the link: they only add GPU time."""
     assert len(sizes) == len(target)
@@ -115,6 +116,8 @@ def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d
         lane = max(t_h2d, t_gpu)
     elif n_slots >= 2:
         first = n_g[0]
+        if slot_params:                      # subgroups stream through the slots in pieces
+            first = min(first, slot_params)
         lead = 12.0 * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s
         lane = max(t_h2d, lead + t_d2h, t_gpu)
     else:

@@ -15,6 +15,8 @@ DOS_HOST_PINNED, DOS_DEVICE = 0, 1
 DOS_ON_CPU, DOS_ON_GPU = 0, 1
 DOS_PLAN_STRIDE, DOS_PLAN_BALANCED = 0, 1
 DOS_CTX_PROFILE = 1
+DOS_CTX_UPLOAD_DMA = 2
+DOS_CTX_SPIN_WAIT = 4
 
 
 class dos_subgroup(C.Structure):
@@ -59,7 +61,8 @@ class dos_phase_stats(C.Structure):
     _fields_ = [("wall_s", C.c_double), ("h2d_bytes", C.c_double), ("d2h_bytes", C.c_double),
                 ("h2d_busy_s", C.c_double), ("d2h_busy_s", C.c_double), ("gpu_busy_s", C.c_double),
                 ("duplex_overlap_s", C.c_double), ("cpu_lane_s", C.c_double),
-                ("gpu_lane_s", C.c_double), ("params_gpu", C.c_uint64), ("params_cpu", C.c_uint64),
+                ("gpu_lane_s", C.c_double), ("cpu_compute_s", C.c_double), ("cpu_wait_s", C.c_double),
+                ("cpu_enqueue_s", C.c_double), ("params_gpu", C.c_uint64), ("params_cpu", C.c_uint64),
                 ("params_resident", C.c_uint64), ("n_gpu", C.c_int32), ("n_cpu", C.c_int32),
                 ("n_resident", C.c_int32), ("n_slots", C.c_int32), ("n_pieces", C.c_int32),
                 ("host_threads", C.c_int32)]
@@ -79,7 +82,7 @@ SIGNATURES = {
                                      C.POINTER(dos_plan)]),
     "dos_plan_cost": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(C.c_uint64),
                                 C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), C.c_int32, C.c_int32,
-                                C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+                                C.c_uint64, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "dos_ctx_create": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(dos_ctx_config)]),
     "dos_ctx_destroy": (None, [C.c_void_p]),
     "dos_run_update_phase": (C.c_int, [C.c_void_p, C.POINTER(dos_subgroup), C.c_int32,
@@ -88,6 +91,7 @@ SIGNATURES = {
     "dos_calibrate": (C.c_int, [C.c_void_p, C.POINTER(dos_cost_model)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
+    "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
     "dos_last_hip_error": (C.c_char_p, []),
     "dos_version": (C.c_int32, []),
@@ -104,7 +108,16 @@ def load():
     if not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build_library()
+    # Streams and device pointers come from PyTorch, so libdos must bind to the
+    # HIP runtime PyTorch ships: load torch's runtime first, then the library
+    # (same soname, the loader then shares one copy), and refuse two runtimes.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
+    with open("/proc/self/maps") as f:
+        runtimes = {ln.split()[-1] for ln in f if "libamdhip64" in ln}
+    if len(runtimes) > 1:
+        raise ImportError("two HIP runtimes are mapped (%s): import torch before anything that loads "
+                          "libamdhip64" % ", ".join(sorted(runtimes)))
     for name, (res, args) in SIGNATURES.items():
         fn = getattr(lib, name)          # AttributeError = a declared symbol is missing
         fn.restype = res
@@ -218,13 +231,14 @@ def dos_plan_subgroups(cm: dos_cost_model, sizes, gpu_budget_bytes: int, mode: i
     return pl
 
 
-def dos_plan_cost(cm: dos_cost_model, sizes, targets, n_slots: int, residents=None):
+def dos_plan_cost(cm: dos_cost_model, sizes, targets, n_slots: int, residents=None, slot_params: int = 0):
     n = len(sizes)
     arr = (C.c_uint64 * max(n, 1))(*[int(s) for s in sizes])
     tg = (C.c_uint8 * max(n, 1))(*[int(t) for t in targets])
     rs = (C.c_uint8 * max(n, 1))(*[int(r) for r in residents]) if residents is not None else None
     pred, low = C.c_double(), C.c_double()
-    check(load().dos_plan_cost(C.byref(cm), arr, tg, rs, n, int(n_slots), C.byref(pred), C.byref(low)),
+    check(load().dos_plan_cost(C.byref(cm), arr, tg, rs, n, int(n_slots), int(slot_params), C.byref(pred),
+                               C.byref(low)),
           "dos_plan_cost")
     return pred.value, low.value
 
@@ -237,6 +251,10 @@ def dos_pinned_alloc(nbytes: int) -> int:
 
 def dos_pinned_free(ptr: int) -> None:
     check(load().dos_pinned_free(C.c_void_p(ptr)), "dos_pinned_free")
+
+
+def dos_host_prefault(ptr: int, nbytes: int, threads: int = 1) -> None:
+    check(load().dos_host_prefault(C.c_void_p(ptr), int(nbytes), int(threads)), "dos_host_prefault")
 
 
 class Context:

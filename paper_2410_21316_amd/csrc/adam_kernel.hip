@@ -178,6 +178,21 @@ __global__ __launch_bounds__(512) void adam_kernel_octets(float* __restrict__ p,
   }
 }
 
+// Pull copy: lanes read 16 bytes each from (pinned, device-mapped) host memory
+// and write them to device memory.  Used for the 16-bit parameter uploads of the
+// host lane, which would otherwise queue behind the bulk prefetches on the DMA
+// engine that serves the host-to-device direction.
+__global__ __launch_bounds__(256) void pull_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                        uint64_t n_vec, uint16_t* __restrict__ dst16,
+                                                        const uint16_t* __restrict__ src16, uint64_t n16) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
+    dst[i] = __builtin_nontemporal_load(src + i);
+  // trailing 16-bit words (fewer than 8)
+  const uint64_t t = n_vec * 8 + threadIdx.x;
+  if (blockIdx.x == 0 && t < n16) dst16[t] = src16[t];
+}
+
 template <bool NTL, bool NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, hipStream_t st_, float* p, float* m, float* v,
                          const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s) {
@@ -221,6 +236,23 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     note_hip_error((int)e, "launch of the fused AdamW kernel");
+    return DOS_EHIP;
+  }
+  return DOS_OK;
+}
+
+dos_status launch_pull_copy_u16(uint16_t* dst_dev, const uint16_t* src_host, uint64_t n, void* stream) {
+  if (n == 0) return DOS_OK;
+  const uint64_t n_vec = n >> 3;
+  uint64_t blocks = (n_vec + 255) / 256;
+  if (blocks > 64) blocks = 64;  // a few CUs keep enough reads in flight for the host link
+  if (blocks == 0) blocks = 1;
+  hipLaunchKernelGGL(pull_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                     reinterpret_cast<u32x4*>(dst_dev), reinterpret_cast<const u32x4*>(src_host), n_vec, dst_dev,
+                     src_host, n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    note_hip_error((int)e, "launch of the upload copy kernel");
     return DOS_EHIP;
   }
   return DOS_OK;

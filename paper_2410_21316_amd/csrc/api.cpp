@@ -4,6 +4,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <thread>
+#include <vector>
+
 #include "dos_internal.h"
 
 namespace dos {
@@ -56,6 +60,28 @@ dos_status dos_pinned_free(void* ptr) {
     (void)hipGetLastError();
     return DOS_EHIP;
   }
+  return DOS_OK;
+}
+
+dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {
+  if (!ptr && bytes) return DOS_EINVAL;
+  if (bytes == 0) return DOS_OK;
+  int T = threads < 1 ? 1 : (threads > 256 ? 256 : threads);
+  const uint64_t page = 4096;
+  const uint64_t pages = (bytes + page - 1) / page;
+  if ((uint64_t)T > pages) T = (int)pages;
+  std::vector<std::thread> pool;
+  std::atomic<uint64_t> sink{0};
+  const volatile unsigned char* base = static_cast<const volatile unsigned char*>(ptr);
+  for (int t = 0; t < T; ++t) {
+    const uint64_t lo = pages * t / T, hi = pages * (t + 1) / T;
+    pool.emplace_back([=, &sink] {
+      uint64_t acc = 0;
+      for (uint64_t pg = lo; pg < hi; ++pg) acc += base[pg * page];
+      sink.fetch_add(acc, std::memory_order_relaxed);
+    });
+  }
+  for (auto& th : pool) th.join();
   return DOS_OK;
 }
 

@@ -25,6 +25,10 @@ dos_status check_subgroup_pointers(const dos_subgroup* sg);
 dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                        const AdamScalars& s, void* stream, const dos_launch_cfg* cfg);
 
+// Enqueues a copy kernel that reads n 16-bit words from pinned (device-mapped)
+// host memory and writes them to device memory; both pointers 16-byte aligned.
+dos_status launch_pull_copy_u16(uint16_t* dst_dev, const uint16_t* src_host, uint64_t n, void* stream);
+
 // Host update of elements [0, n) on the calling thread (vectorised, bit-identical
 // to the device kernel).
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,

@@ -6,9 +6,10 @@
 //                 j mod n_slots:  H2D stream: wait(slot free), copy p, m, v (and
 //                 g when it is host-resident) in, record(ready);  compute stream:
 //                 wait(ready), fused AdamW kernel, record(done);  D2H stream:
-//                 wait(done), copy p, m, v back, record(free).  Everything is
-//                 enqueued up front; the three streams and their events form the
-//                 pipeline, prefetch and flush run full duplex.  Static residents
+//                 wait(done), copy p, m, v back, record(free).  The calling
+//                 thread drives this as a software pipeline with a bounded
+//                 look-ahead (prefetch j+1, then kernel + flush j once j has
+//                 landed); prefetch and flush run full duplex.  Static residents
 //                 (state already in device memory) are updated in place, last.
 //   host lane  -- persistent worker threads take chunks of the CPU-planned
 //                 subgroups, run the host AdamW (which writes the 16-bit
@@ -57,7 +58,6 @@ struct dos_ctx {
   int device = 0;
   int flags = 0;
   hipStream_t h2d = nullptr, comp = nullptr, d2h = nullptr, upl = nullptr;
-  bool own_h2d = false, own_comp = false, own_d2h = false, own_upl = false;
   // staging ring on the device
   char* slot_mem = nullptr;
   uint64_t slot_params = 0, slot_stride = 0;
@@ -89,6 +89,8 @@ struct dos_ctx {
   std::atomic<int> job_error{0};
   std::mutex upl_mu;
   clk::time_point cpu_first, cpu_last;
+  struct alignas(64) LaneTimes { double compute = 0, wait = 0, enqueue = 0; };
+  std::vector<LaneTimes> lane_times;  // one per worker, reset every phase
   std::atomic<bool> cpu_started{false};
   // scratch lists reused across phases (reserved at creation)
   std::vector<Chunk> chunks;
@@ -97,6 +99,32 @@ struct dos_ctx {
 };
 
 namespace {
+
+// Streams the library creates are created once per device and kept until the
+// process ends: on this platform a copy stream that is destroyed and created
+// again can end up sharing a DMA engine with the stream of the other direction
+// (prefetches and flushes then serialise); the first set does not.
+struct DeviceStreams {
+  hipStream_t s[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool made = false;
+};
+std::mutex g_streams_mu;
+DeviceStreams g_streams[64];
+
+hipError_t library_streams(int device, hipStream_t out[4]) {
+  if (device < 0 || device >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_streams_mu);
+  DeviceStreams& d = g_streams[device];
+  if (!d.made) {
+    for (int i = 0; i < 4; ++i) {
+      hipError_t e = hipStreamCreateWithFlags(&d.s[i], hipStreamNonBlocking);
+      if (e != hipSuccess) return e;
+    }
+    d.made = true;
+  }
+  for (int i = 0; i < 4; ++i) out[i] = d.s[i];
+  return hipSuccess;
+}
 
 #define HIP_TRY(ctx, call, what)                \
   do {                                          \
@@ -109,7 +137,7 @@ namespace {
     }                                           \
   } while (0)
 
-void worker_main(dos_ctx* c, int /*tid*/) {
+void worker_main(dos_ctx* c, int tid) {
   (void)hipSetDevice(c->device);
   uint64_t seen = 0;
   for (;;) {
@@ -121,6 +149,8 @@ void worker_main(dos_ctx* c, int /*tid*/) {
     }
     const std::vector<Chunk>& chunks = *c->job_chunks;
     const int64_t total = (int64_t)chunks.size();
+    dos_ctx::LaneTimes& lt = c->lane_times[tid];
+    lt = dos_ctx::LaneTimes();
     for (;;) {
       const int64_t ci = c->next_chunk.fetch_add(1);
       if (ci >= total || c->job_error.load()) break;
@@ -129,6 +159,7 @@ void worker_main(dos_ctx* c, int /*tid*/) {
       const dos_subgroup& sg = c->job_sgs[ch.sg];
       const int r = (int)(ci % c->ring_n);
       // the ring entry is free once the upload of chunk ci - ring_n has landed
+      const auto tw0 = clk::now();
       if (ci >= c->ring_n) {
         while (c->ring_seq[r].load(std::memory_order_acquire) != ci - c->ring_n) {
           if (c->job_error.load()) break;
@@ -141,11 +172,18 @@ void worker_main(dos_ctx* c, int /*tid*/) {
         }
       }
       uint16_t* out = reinterpret_cast<uint16_t*>(c->stage + (uint64_t)r * c->chunk_params * 2);
+      const auto tw1 = clk::now();
       dos::host_adam_range(sg.p + ch.off, sg.m + ch.off, sg.v + ch.off, sg.g + ch.off, out, ch.cnt,
                            c->job_scalars);
+      const auto tw2 = clk::now();
       {
         std::lock_guard<std::mutex> lk(c->upl_mu);
-        hipError_t e = hipMemcpyAsync(sg.p_lp + ch.off, out, ch.cnt * 2, hipMemcpyHostToDevice, c->upl);
+        hipError_t e = hipSuccess;
+        if (c->flags & DOS_CTX_UPLOAD_DMA) {
+          e = hipMemcpyAsync(sg.p_lp + ch.off, out, ch.cnt * 2, hipMemcpyHostToDevice, c->upl);
+        } else if (dos::launch_pull_copy_u16(sg.p_lp + ch.off, out, ch.cnt, c->upl) != DOS_OK) {
+          e = hipErrorLaunchFailure;
+        }
         if (e == hipSuccess) e = hipEventRecord(c->ring_ev[r], c->upl);
         if (e != hipSuccess) {
           dos::note_hip_error((int)e, "upload of 16-bit parameters");
@@ -153,6 +191,10 @@ void worker_main(dos_ctx* c, int /*tid*/) {
         }
       }
       c->ring_seq[r].store(ci, std::memory_order_release);
+      const auto tw3 = clk::now();
+      lt.wait += secs(tw0, tw1);
+      lt.compute += secs(tw1, tw2);
+      lt.enqueue += secs(tw2, tw3);
     }
     {
       std::lock_guard<std::mutex> lk(c->mu);
@@ -181,10 +223,6 @@ void destroy(dos_ctx* c) {
     if (e) (void)hipEventDestroy(e);
   if (c->t0) (void)hipEventDestroy(c->t0);
   if (c->t1) (void)hipEventDestroy(c->t1);
-  if (c->own_h2d && c->h2d) (void)hipStreamDestroy(c->h2d);
-  if (c->own_comp && c->comp) (void)hipStreamDestroy(c->comp);
-  if (c->own_d2h && c->d2h) (void)hipStreamDestroy(c->d2h);
-  if (c->own_upl && c->upl) (void)hipStreamDestroy(c->upl);
   delete c;
 }
 
@@ -258,21 +296,18 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     return DOS_EHIP;
   };
   hipError_t e;
-  struct { void* given; hipStream_t* dst; bool* own; } st[4] = {
-      {cfg->h2d_stream, &c->h2d, &c->own_h2d}, {cfg->compute_stream, &c->comp, &c->own_comp},
-      {cfg->d2h_stream, &c->d2h, &c->own_d2h}, {cfg->upload_stream, &c->upl, &c->own_upl}};
-  for (auto& s : st) {
-    if (s.given) {
-      *s.dst = (hipStream_t)s.given;
-    } else {
-      if ((e = hipStreamCreateWithFlags(s.dst, hipStreamNonBlocking)) != hipSuccess) return fail(e, "hipStreamCreate");
-      *s.own = true;
-    }
-  }
+  struct { void* given; hipStream_t* dst; } st[4] = {{cfg->h2d_stream, &c->h2d}, {cfg->compute_stream, &c->comp},
+                                                     {cfg->d2h_stream, &c->d2h}, {cfg->upload_stream, &c->upl}};
+  hipStream_t lib_streams[4];
+  if ((e = library_streams(c->device, lib_streams)) != hipSuccess) return fail(e, "hipStreamCreate");
+  for (int i = 0; i < 4; ++i) *st[i].dst = st[i].given ? (hipStream_t)st[i].given : lib_streams[i];
   for (int s = 0; s < c->n_slots; ++s) {
-    if ((e = hipEventCreateWithFlags(&c->ready[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    if ((e = hipEventCreateWithFlags(&c->ready[s], hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
+      return fail(e, "hipEventCreate");
     if ((e = hipEventCreateWithFlags(&c->done[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
-    if ((e = hipEventCreateWithFlags(&c->freed[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    // the driver thread sleeps on this one (it must not take a core from the workers)
+    if ((e = hipEventCreateWithFlags(&c->freed[s], hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
+      return fail(e, "hipEventCreate");
   }
   c->ring_ev.assign(ring_n, nullptr);
   c->ring_seq = std::vector<std::atomic<int64_t>>(ring_n);
@@ -287,6 +322,7 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
   }
   c->chunks.reserve(1 << 16);
   c->pieces.reserve(1 << 14);
+  c->lane_times.resize(c->T);
   c->workers.reserve(c->T);
   for (int t = 0; t < c->T; ++t) c->workers.emplace_back(worker_main, c, t);
   *out = c;
@@ -376,47 +412,85 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
   auto enqueue_gpu = [&]() -> dos_status {
     HIP_TRY(c, hipEventRecord(c->t0, c->h2d), "hipEventRecord");
     // the other streams start no earlier than t0 (keeps the timeline comparable)
-    for (size_t j = 0; j < pieces.size(); ++j) {
+    struct SlotPtrs {
+      float *p, *m, *v;
+      uint16_t* g;
+    };
+    auto slot_of = [&](size_t j) {
+      char* base = c->slot_mem + (uint64_t)(j % (size_t)c->n_slots) * c->slot_stride;
+      return SlotPtrs{(float*)base, (float*)(base + 4 * c->slot_params), (float*)(base + 8 * c->slot_params),
+                      (uint16_t*)(base + 12 * c->slot_params)};
+    };
+    // prefetch of piece j into its slot (H2D stream)
+    auto enqueue_prefetch = [&](size_t j) -> dos_status {
       const Piece& pc = pieces[j];
       const dos_subgroup& sg = sgs[pc.sg];
       const int s = (int)(j % (size_t)c->n_slots);
-      char* base = c->slot_mem + (uint64_t)s * c->slot_stride;
-      float* sp = (float*)base;
-      float* sm = (float*)(base + 4 * c->slot_params);
-      float* sv = (float*)(base + 8 * c->slot_params);
-      uint16_t* sgd = (uint16_t*)(base + 12 * c->slot_params);
+      const SlotPtrs sl = slot_of(j);
       const size_t fb = pc.cnt * 4;
       hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
-      if (j >= (size_t)c->n_slots) HIP_TRY(c, hipStreamWaitEvent(c->h2d, c->freed[s], 0), "hipStreamWaitEvent");
+      // the slot is free once the flush of piece j - n_slots has landed (host wait:
+      // no stream ever holds a long chain of blocked commands)
+      if (j >= (size_t)c->n_slots) HIP_TRY(c, hipEventSynchronize(c->freed[s]), "hipEventSynchronize");
       if (pe) HIP_TRY(c, hipEventRecord(pe[0], c->h2d), "hipEventRecord");
-      HIP_TRY(c, hipMemcpyAsync(sp, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of p");
-      HIP_TRY(c, hipMemcpyAsync(sm, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of m");
-      HIP_TRY(c, hipMemcpyAsync(sv, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of v");
-      const uint16_t* gdev = sg.g + pc.off;
-      if (sg.grad_loc == DOS_HOST_PINNED) {
-        HIP_TRY(c, hipMemcpyAsync(sgd, sg.g + pc.off, pc.cnt * 2, hipMemcpyHostToDevice, c->h2d), "prefetch of g");
-        gdev = sgd;
-      }
+      HIP_TRY(c, hipMemcpyAsync(sl.p, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of p");
+      HIP_TRY(c, hipMemcpyAsync(sl.m, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of m");
+      HIP_TRY(c, hipMemcpyAsync(sl.v, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of v");
+      if (sg.grad_loc == DOS_HOST_PINNED)
+        HIP_TRY(c, hipMemcpyAsync(sl.g, sg.g + pc.off, pc.cnt * 2, hipMemcpyHostToDevice, c->h2d), "prefetch of g");
       if (pe) HIP_TRY(c, hipEventRecord(pe[1], c->h2d), "hipEventRecord");
       HIP_TRY(c, hipEventRecord(c->ready[s], c->h2d), "hipEventRecord");
-
+      return DOS_OK;
+    };
+    // kernel over the slot (compute stream) and flush back to the host (D2H stream)
+    auto enqueue_update_and_flush = [&](size_t j) -> dos_status {
+      const Piece& pc = pieces[j];
+      const dos_subgroup& sg = sgs[pc.sg];
+      const int s = (int)(j % (size_t)c->n_slots);
+      const SlotPtrs sl = slot_of(j);
+      const size_t fb = pc.cnt * 4;
+      hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
+      const uint16_t* gdev = (sg.grad_loc == DOS_HOST_PINNED) ? sl.g : sg.g + pc.off;
       HIP_TRY(c, hipStreamWaitEvent(c->comp, c->ready[s], 0), "hipStreamWaitEvent");
       if (pe) HIP_TRY(c, hipEventRecord(pe[2], c->comp), "hipEventRecord");
-      dos_status k = dos::launch_adam(sp, sm, sv, gdev, sg.p_lp + pc.off, pc.cnt, sc, c->comp, nullptr);
+      dos_status k = dos::launch_adam(sl.p, sl.m, sl.v, gdev, sg.p_lp + pc.off, pc.cnt, sc, c->comp, nullptr);
       if (k != DOS_OK) {
         c->sticky = k;
         return k;
       }
       if (pe) HIP_TRY(c, hipEventRecord(pe[3], c->comp), "hipEventRecord");
       HIP_TRY(c, hipEventRecord(c->done[s], c->comp), "hipEventRecord");
-
       HIP_TRY(c, hipStreamWaitEvent(c->d2h, c->done[s], 0), "hipStreamWaitEvent");
       if (pe) HIP_TRY(c, hipEventRecord(pe[4], c->d2h), "hipEventRecord");
-      HIP_TRY(c, hipMemcpyAsync(sg.p + pc.off, sp, fb, hipMemcpyDeviceToHost, c->d2h), "flush of p");
-      HIP_TRY(c, hipMemcpyAsync(sg.m + pc.off, sm, fb, hipMemcpyDeviceToHost, c->d2h), "flush of m");
-      HIP_TRY(c, hipMemcpyAsync(sg.v + pc.off, sv, fb, hipMemcpyDeviceToHost, c->d2h), "flush of v");
+      HIP_TRY(c, hipMemcpyAsync(sg.p + pc.off, sl.p, fb, hipMemcpyDeviceToHost, c->d2h), "flush of p");
+      HIP_TRY(c, hipMemcpyAsync(sg.m + pc.off, sl.m, fb, hipMemcpyDeviceToHost, c->d2h), "flush of m");
+      HIP_TRY(c, hipMemcpyAsync(sg.v + pc.off, sl.v, fb, hipMemcpyDeviceToHost, c->d2h), "flush of v");
       if (pe) HIP_TRY(c, hipEventRecord(pe[5], c->d2h), "hipEventRecord");
       HIP_TRY(c, hipEventRecord(c->freed[s], c->d2h), "hipEventRecord");
+      return DOS_OK;
+    };
+    // Software pipeline driven by the calling thread.  The prefetch of piece j+1
+    // is enqueued before the flush of piece j, and the flush only once piece j
+    // has landed: when the D2H stream submits a copy, the DMA engine that serves
+    // the prefetches is busy, so the runtime (which picks a free engine per
+    // stream at submission time) never puts both directions on one engine.
+    const size_t np = pieces.size();
+    if (np > 0) {
+      dos_status r = enqueue_prefetch(0);
+      if (r != DOS_OK) return r;
+    }
+    for (size_t j = 0; j < np; ++j) {
+      if (c->n_slots >= 2 && j + 1 < np) {
+        dos_status r = enqueue_prefetch(j + 1);
+        if (r != DOS_OK) return r;
+      }
+      HIP_TRY(c, hipEventSynchronize(c->ready[j % (size_t)c->n_slots]), "hipEventSynchronize");
+      dos_status r = enqueue_update_and_flush(j);
+      if (r != DOS_OK) return r;
+      if (c->n_slots < 2 && j + 1 < np) {  // one slot: strictly serial
+        r = enqueue_prefetch(j + 1);
+        if (r != DOS_OK) return r;
+      }
     }
     // static residents, placed last: their kernels overlap the tail transfers
     for (int k = 0; k < n_sg; ++k) {
@@ -476,6 +550,12 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
     stats->n_slots = c->n_slots;
     stats->n_pieces = (int32_t)pieces.size();
     stats->host_threads = c->T;
+    if (!chunks.empty())
+      for (const auto& lt : c->lane_times) {
+        stats->cpu_compute_s += lt.compute;
+        stats->cpu_wait_s += lt.wait;
+        stats->cpu_enqueue_s += lt.enqueue;
+      }
     if (prof && !pieces.empty()) {
       std::vector<std::pair<double, double>> up, down;
       double hb = 0, db = 0, gb = 0;

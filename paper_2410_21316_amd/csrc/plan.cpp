@@ -11,8 +11,13 @@
 
 namespace {
 
-constexpr int kMaxSlots = 4;
+// Three slots are enough to keep prefetch, kernel and flush of consecutive pieces
+// overlapped; on MI355X more outstanding prefetches slow the flushes down.
+constexpr int kMaxSlots = 3;
 constexpr uint64_t kMinSlotParams = 1u << 16;
+// Pieces of 16 Mi parameters (192 MiB of FP32 state) copy at full link rate and
+// keep fill/drain of the pipeline and the wait of anything queued behind it short.
+constexpr uint64_t kPieceParams = 16u << 20;
 
 struct Cost {
   double predicted, lower;
@@ -31,7 +36,7 @@ bool valid_cost_model(const dos_cost_model* cm) {
 // launch.  Residents: GPU time only.  With >= 2 slots the lanes overlap and only
 // the first prefetch + kernel lead the D2H lane; with one slot they serialise.
 Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* target,
-              const uint8_t* resident, int n, int n_slots) {
+              const uint8_t* resident, int n, int n_slots, uint64_t slot_params) {
   double NG = 0, NC = 0, NR = 0, first = -1;
   int cg = 0, cr = 0;
   for (int i = 0; i < n; ++i) {
@@ -55,6 +60,7 @@ Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* ta
   if (cg == 0) {
     lane = std::max(t_h2d, t_gpu);
   } else if (n_slots >= 2) {
+    if (slot_params > 0 && first > (double)slot_params) first = (double)slot_params;  // pieces
     const double lead = 12.0 * first / cm.h2d_Bps + first / cm.gpu_params_per_s + cm.launch_overhead_s;
     lane = std::max(std::max(t_h2d, lead + t_d2h), t_gpu);
   } else {
@@ -67,14 +73,14 @@ Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* ta
 
 extern "C" dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* target,
                                     const uint8_t* resident, int32_t n_sg, int32_t n_slots,
-                                    double* predicted_s, double* lower_bound_s) {
+                                    uint64_t slot_params, double* predicted_s, double* lower_bound_s) {
   if (!valid_cost_model(cm) || n_sg < 0 || n_slots < 1 || !predicted_s || !lower_bound_s) return DOS_EINVAL;
   if (n_sg > 0 && (!sizes || !target)) return DOS_EINVAL;
   for (int i = 0; i < n_sg; ++i) {
     if (target[i] > DOS_ON_GPU) return DOS_EINVAL;
     if (resident && resident[i] && target[i] != DOS_ON_GPU) return DOS_ESTATE;
   }
-  const Cost c = evaluate(*cm, sizes, target, resident, n_sg, n_slots);
+  const Cost c = evaluate(*cm, sizes, target, resident, n_sg, n_slots, slot_params);
   *predicted_s = c.predicted;
   *lower_bound_s = c.lower;
   return DOS_OK;
@@ -96,16 +102,13 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   uint64_t slot_params;
   int n_slots;
   const uint64_t s_pad = (s_max + 63) & ~(uint64_t)63;  // keeps every slot array 16-byte aligned
-  if (s_pad > 0 && gpu_budget_bytes / bpp / 2 >= s_pad) {
-    slot_params = s_pad;
-    n_slots = (int)std::min<uint64_t>(kMaxSlots, gpu_budget_bytes / (bpp * s_pad));
+  const uint64_t want = std::min<uint64_t>(s_pad, kPieceParams);  // subgroups stream through in pieces
+  if (want > 0 && gpu_budget_bytes / bpp / 2 >= want) {
+    slot_params = want;
+    n_slots = (int)std::min<uint64_t>(kMaxSlots, gpu_budget_bytes / (bpp * want));
   } else {
-    slot_params = (gpu_budget_bytes / (3 * bpp)) & ~(uint64_t)0xFFFF;  // multiple of 64 Ki
-    n_slots = 3;
-    if (s_pad > 0 && slot_params > s_pad) {  // one whole subgroup fits, two do not
-      slot_params = s_pad;
-      n_slots = 1;
-    }
+    slot_params = (gpu_budget_bytes / (kMaxSlots * bpp)) & ~(uint64_t)0xFFFF;  // multiple of 64 Ki
+    n_slots = kMaxSlots;
   }
   if (n_sg > 0 && slot_params < kMinSlotParams) return DOS_EBUDGET;
 
@@ -136,12 +139,25 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   }
 
   auto cost_of = [&](const std::vector<uint8_t>& t) {
-    return evaluate(*cm, sizes, t.data(), resident.data(), n_sg, n_slots);
+    return evaluate(*cm, sizes, t.data(), resident.data(), n_sg, n_slots, slot_params);
   };
 
   if (mode == DOS_PLAN_STRIDE) {
     for (int i = 0; i < n_dyn; ++i)
       if (k >= 1 && (i + 1) % k == 0) target[i] = DOS_ON_GPU;
+  } else if (n_dyn <= 16) {
+    // few subgroups: every assignment is tried
+    std::vector<uint8_t> best = target, cand = target;
+    double best_cost = cost_of(best).predicted;
+    for (uint32_t bits = 1; bits < (1u << n_dyn); ++bits) {
+      for (int i = 0; i < n_dyn; ++i) cand[i] = (bits >> i) & 1u;
+      const double cc = cost_of(cand).predicted;
+      if (cc < best_cost) {
+        best_cost = cc;
+        best = cand;
+      }
+    }
+    target = best;
   } else {
     // evenly spread c GPU subgroups among the dynamic ones (for c = n/k this is
     // Algorithm 1's stride pattern), pick the best count ...

@@ -139,11 +139,13 @@ def test_validation_errors_leave_state_untouched(hp):
 def test_transfers_overlap_full_duplex(hp):
     """Prefetch of the next subgroup and flush of the previous one run at the
     same time (Section 4.1); measured with the context's profiling events."""
-    sizes = [4_000_000] * 6
-    stats = run_phase_case(sizes, [1] * 6, None, 3, 4_000_000, hp, steps=1, grad_on_device=[1] * 6,
+    sizes = [32 << 20] * 6
+    stats = run_phase_case(sizes, [1] * 6, None, 3, 16 << 20, hp, steps=2, grad_on_device=[1] * 6,
                            flags=dos.DOS_CTX_PROFILE)
-    assert stats.duplex_overlap_s > 0.0
-    assert stats.n_pieces == 6
+    assert stats.n_pieces == 12
+    print({k: v for k, v in stats.asdict().items() if k.endswith("_s")})
+    # a good part of the flush time runs concurrently with prefetches
+    assert stats.duplex_overlap_s > stats.d2h_busy_s / 4 > 0.0
 
 
 def test_calibration_reports_plausible_rates():

@@ -1,0 +1,210 @@
+"""dos_plan_subgroups / dos_plan_cost (host-only part of the C ABI) against the
+planner reference: Eq. 1 and Algorithm 1's stride placement, the cost function,
+and the balanced mode against brute force."""
+import ctypes as C
+import random
+
+import pytest
+
+import paper_2410_21316_amd as dos
+from oracle import plan_ref as ref
+
+G = 1e9
+
+
+def cm_from_paper_units(B, Ug, Uc, Dc):
+    """The paper quotes all four rates in FP32 parameters per second; the C ABI
+    takes the link in bytes per second (4 bytes per FP32 parameter)."""
+    return dos.cost_model(4 * B, 4 * B, Ug, Uc, Dc, 0.0)
+
+
+def test_stride_mode_reproduces_the_papers_worked_example():
+    """Section 5.4: (B, U_g, U_c, D_c) = (3, 35, 2, 8.7) G params/s gives k = 2,
+    'every alternate subgroup'."""
+    cm = cm_from_paper_units(3 * G, 35 * G, 2 * G, 8.7 * G)
+    sizes = [100_000_000] * 70
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_STRIDE)
+    assert plan.c.stride_k == 2
+    assert plan.c.stride_k_real == pytest.approx(ref.stride_k_real(3 * G, 35 * G, 2 * G, 8.7 * G), rel=1e-12)
+    assert plan.c.stride_k_real == pytest.approx(2.2945, abs=5e-4)
+    assert plan.targets == ref.stride_targets(70, 2)
+    assert plan.orders == list(range(70))
+    assert sum(plan.targets) == 35                     # 50 % on the GPU
+
+
+@pytest.mark.parametrize("rates", [(4.6, 180, 1.5, 20), (14, 190, 7.5, 0), (3, 35, 2, 8.7), (12, 25, 8, 15.5),
+                                   (1, 100, 0.3, 5), (50, 200, 100, 0)])
+def test_stride_mode_matches_reference_for_any_rates(rates):
+    B, Ug, Uc, Dc = (x * G for x in rates)
+    cm = cm_from_paper_units(B, Ug, Uc, Dc)
+    for n_sg in (1, 2, 7, 33, 130):
+        plan = dos.dos_plan_subgroups(cm, [50_000_000] * n_sg, 8 * 10**9, dos.DOS_PLAN_STRIDE)
+        k = ref.stride_k(B, Ug, Uc, Dc if Dc else float("inf"))
+        assert plan.c.stride_k == k
+        assert plan.targets == ref.stride_targets(n_sg, k)
+
+
+def test_stride_does_not_depend_on_subgroup_size():
+    """Section 4.2: k is independent of the subgroup size."""
+    cm = cm_from_paper_units(3 * G, 35 * G, 2 * G, 8.7 * G)
+    base = dos.dos_plan_subgroups(cm, [100_000_000] * 24, 64 * 10**9, dos.DOS_PLAN_STRIDE)
+    for scale in (0.5, 2, 4, 10):
+        other = dos.dos_plan_subgroups(cm, [int(100_000_000 * scale)] * 24, 64 * 10**9, dos.DOS_PLAN_STRIDE)
+        assert other.targets == base.targets and other.c.stride_k == base.c.stride_k
+
+
+def test_update_figure_placement_with_residents_last():
+    """Section 4.1 figure: 8 subgroups, stride 3, two static residents placed
+    last -> GPU set {S3, S6, S7, S8}.  Rates chosen so that Eq. 1 gives 3."""
+    B, Ug, Uc, Dc = 3 * G, 35 * G, 2.8 * G, 8.7 * G
+    assert ref.stride_k(B, Ug, Uc, Dc) == 3
+    sizes = [10_000_000] * 8
+    slots = 3 * 12 * 10_000_000
+    plan = dos.dos_plan_subgroups(cm_from_paper_units(B, Ug, Uc, Dc), sizes, slots + 2 * 12 * 10_000_000,
+                                  dos.DOS_PLAN_STRIDE, n_resident_max=2)
+    assert plan.residents == [0, 0, 0, 0, 0, 0, 1, 1]
+    assert [i for i, t in enumerate(plan.targets) if t] == [2, 5, 6, 7]
+    assert plan.targets == ref.stride_targets(8, 3, residents=(6, 7))
+
+
+COST = dict(h2d_Bps=55e9, d2h_Bps=48e9, gpu_params_per_s=190e9, cpu_params_per_s=7e9, launch_overhead_s=8e-6)
+
+
+def test_cost_function_matches_reference():
+    rng = random.Random(7)
+    cm = dos.cost_model(COST["h2d_Bps"], COST["d2h_Bps"], COST["gpu_params_per_s"], COST["cpu_params_per_s"], 0.0,
+                        COST["launch_overhead_s"])
+    for _ in range(200):
+        n = rng.randint(1, 14)
+        sizes = [rng.randint(1, 400) * 1_000_000 for _ in range(n)]
+        tgt = [rng.randint(0, 1) for _ in range(n)]
+        n_res = rng.randint(0, 2)
+        res = [0] * n
+        for i in range(n - 1, max(-1, n - 1 - n_res), -1):
+            res[i] = 1
+            tgt[i] = 1
+        slots = rng.choice([1, 2, 3])
+        sp = rng.choice([0, 16 << 20])
+        got = dos.dos_plan_cost(cm, sizes, tgt, slots, res, sp)
+        want = ref.phase_cost(sizes, tgt, n_slots=slots, resident=[i for i in range(n) if res[i]], slot_params=sp,
+                              **COST)
+        assert got[0] == pytest.approx(want[0], rel=1e-12)
+        assert got[1] == pytest.approx(want[1], rel=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_balanced_mode_is_close_to_the_brute_force_optimum(seed):
+    """For up to 12 subgroups of random, unequal sizes the planner finds the
+    exhaustive optimum of the cost function."""
+    rng = random.Random(seed)
+    n = rng.randint(4, 12)
+    sizes = [rng.randint(40, 160) * 1_000_000 for _ in range(n)]
+    cost = dict(COST)
+    cost["cpu_params_per_s"] = rng.choice([1e9, 3e9, 7e9, 20e9])
+    cost["d2h_Bps"] = rng.choice([24e9, 48e9])
+    cm = dos.cost_model(cost["h2d_Bps"], cost["d2h_Bps"], cost["gpu_params_per_s"], cost["cpu_params_per_s"], 0.0,
+                        cost["launch_overhead_s"])
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
+    best, _ = ref.brute_force_plan(sizes, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost)
+    mine, low = ref.phase_cost(sizes, plan.targets, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost)
+    assert plan.c.predicted_s == pytest.approx(mine, rel=1e-12)
+    assert plan.c.lower_bound_s == pytest.approx(low, rel=1e-12)
+    assert mine <= best * (1 + 1e-12)
+
+
+def test_balanced_mode_heuristic_gap_beyond_sixteen_subgroups():
+    """18 unequal subgroups (heuristic search): within 5 % of brute force."""
+    rng = random.Random(99)
+    sizes = [rng.randint(40, 160) * 1_000_000 for _ in range(18)]
+    cm = dos.cost_model(COST["h2d_Bps"], COST["d2h_Bps"], COST["gpu_params_per_s"], 3e9, 0.0, COST["launch_overhead_s"])
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
+    cost = {**COST, "cpu_params_per_s": 3e9}
+    best, _ = ref.brute_force_plan(sizes, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost)
+    assert plan.c.predicted_s <= best * 1.05
+
+
+def test_balanced_mode_on_equal_subgroups_beats_every_stride():
+    sizes = [100_000_000] * 130
+    cm = dos.cost_model(55e9, 48e9, 190e9, 7e9, 0.0, 8e-6)
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
+    for k in range(1, 9):
+        t = ref.stride_targets(130, k)
+        c, _ = ref.phase_cost(sizes, t, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params,
+                              **{**COST, "cpu_params_per_s": 7e9})
+        assert plan.c.predicted_s <= c * (1 + 1e-12)
+    # the GPU subgroups are spread through the order, not bunched at one end
+    g = [i for i, t in enumerate(plan.targets) if t]
+    assert 0 < len(g) < 130
+    gaps = [b - a for a, b in zip(g, g[1:])]
+    assert max(gaps) <= 2 * (130 // len(g) + 1)
+
+
+def test_slots_follow_the_budget():
+    cm = dos.cost_model(55e9, 48e9, 190e9, 7e9)
+    sizes = [100_000_000] * 10
+    p = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9)
+    assert (p.c.n_slots, p.c.slot_params) == (3, 16 << 20)              # pieces of 16 Mi parameters
+    p = dos.dos_plan_subgroups(cm, [1_000_000] * 10, 40 * 10**9)
+    assert (p.c.n_slots, p.c.slot_params) == (3, 1_000_000)             # whole (small) subgroups
+    p = dos.dos_plan_subgroups(cm, [1_000_001] * 10, 40 * 10**9)
+    assert p.c.slot_params == 1_000_064                                  # padded to 64 elements
+    p = dos.dos_plan_subgroups(cm, sizes, 2 * 12 * (16 << 20))
+    assert (p.c.n_slots, p.c.slot_params) == (2, 16 << 20)
+    p = dos.dos_plan_subgroups(cm, sizes, 100 * 10**6)                   # ~8.3M parameters of staging in all
+    assert p.c.n_slots == 3 and p.c.slot_params == (100 * 10**6 // 36) // 65536 * 65536
+    p = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, bytes_per_param_slot=14)
+    assert p.c.n_slots == 3
+    with pytest.raises(dos.DosError) as e:
+        dos.dos_plan_subgroups(cm, sizes, 1_000_000)
+    assert e.value.status == dos.DOS_EBUDGET
+
+
+def test_residents_take_what_the_budget_leaves():
+    cm = dos.cost_model(55e9, 48e9, 190e9, 7e9)
+    sizes = [100_000_000] * 130
+    p = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, n_resident_max=130)
+    staging = 3 * 12 * (16 << 20)
+    n_res = (40 * 10**9 - staging) // (12 * 100_000_000)
+    assert sum(p.residents) == n_res == 32
+    assert p.residents == [0] * (130 - n_res) + [1] * n_res              # placed last (Section 4.1)
+    assert all(t == 1 for t, r in zip(p.targets, p.residents) if r)
+    p0 = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, n_resident_max=0)
+    assert p.c.predicted_s < p0.c.predicted_s and sum(p0.residents) == 0
+    p5 = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, n_resident_max=5)
+    assert sum(p5.residents) == 5
+
+
+def test_planner_rejects_bad_arguments():
+    lib = dos.load()
+    cm = dos.cost_model(55e9, 48e9, 190e9, 7e9)
+    sizes = (C.c_uint64 * 4)(*[1 << 20] * 4)
+    pl = dos.Plan(4)
+
+    def call(cm_=cm, n=4, budget=10**9, bpp=12, mode=1, nres=0, out=pl.c, sz=sizes):
+        return lib.dos_plan_subgroups(C.byref(cm_) if cm_ is not None else None, sz, n, budget, bpp, mode, nres,
+                                      C.byref(out) if out is not None else None)
+
+    assert call() == dos.DOS_OK
+    assert call(cm_=None) == dos.DOS_EINVAL
+    assert call(out=None) == dos.DOS_EINVAL
+    assert call(n=-1) == dos.DOS_EINVAL
+    assert call(mode=2) == dos.DOS_EINVAL
+    assert call(bpp=13) == dos.DOS_EINVAL
+    assert call(nres=-1) == dos.DOS_EINVAL
+    assert call(sz=None) == dos.DOS_EINVAL
+    assert call(budget=0) == dos.DOS_EBUDGET
+    for field in ("h2d_Bps", "d2h_Bps", "gpu_params_per_s", "cpu_params_per_s"):
+        bad = dos.cost_model(55e9, 48e9, 190e9, 7e9)
+        setattr(bad, field, 0.0)
+        assert call(cm_=bad) == dos.DOS_EINVAL
+        setattr(bad, field, float("nan"))
+        assert call(cm_=bad) == dos.DOS_EINVAL
+    assert call(n=0) == dos.DOS_OK and pl.c.n_sg == 0
+
+
+def test_planner_is_deterministic():
+    cm = dos.cost_model(55e9, 48e9, 190e9, 3e9)
+    sizes = [random.Random(3).randint(50, 150) * 1_000_000 for _ in range(40)]
+    a = dos.dos_plan_subgroups(cm, sizes, 16 * 10**9)
+    b = dos.dos_plan_subgroups(cm, sizes, 16 * 10**9)
+    assert a.targets == b.targets and a.c.predicted_s == b.c.predicted_s
