@@ -109,6 +109,14 @@ def bench_c2(args, dos, torch, np):
     torch.cuda.synchronize()
     stream = torch.cuda.Stream()
     stream.wait_stream(torch.cuda.current_stream())
+    if args.copy_probe:
+        # known-size copy kernel for scaling the profiler's traffic counters: 1 GiB read + 1 GiB written
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        b = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+        for _ in range(3):
+            dos.dos_probe_copy(a.data_ptr(), b.data_ptr(), 1 << 30, stream.cuda_stream)
+        stream.synchronize()
+        del a, b
     wall, ev_s, launches = timed_resident(state, dos, torch, hp_kw, args.steps, args.warmup, stream)
     params_per_step = state.total
     value = params_per_step * args.steps / wall
@@ -323,6 +331,8 @@ def main():
     ap.add_argument("--extra", default="c3,c4", help="comma list of extra workloads (c3, c4) or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB copy kernel three times (reference for traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the update phase needs no inter-GPU exchange; "

@@ -77,10 +77,10 @@ typedef struct dos_hparams {
   int64_t step;
 } dos_hparams;
 
-/* Launch shape of the fused kernel, for tuning sweeps; all-zero = defaults. */
+/* Launch shape of the fused kernel, for tuning sweeps. */
 typedef struct dos_launch_cfg {
   int32_t variant;       /* kernel layout variant, see dos_adam_step_cfg          */
-  int32_t block_threads; /* 0 = default (256); multiple of 64, <= 1024            */
+  int32_t block_threads; /* 0 = default (64); multiple of 64, <= 512              */
   int32_t grid_blocks;   /* 0 = one tile per block; else grid-stride over tiles   */
 } dos_launch_cfg;
 
@@ -92,11 +92,13 @@ typedef struct dos_launch_cfg {
  * state_loc/grad_loc not DOS_DEVICE is DOS_ESTATE), DOS_EALIGN, DOS_EHIP. */
 dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);
 
-/* Same, with an explicit launch shape.  variant 0: each lane handles 4
- * consecutive elements per trip (16-byte FP32 accesses, 8-byte bf16), two trips
- * unrolled; variant 1: one trip; variant 2: four trips; variant 3: each lane
- * handles 8 consecutive elements (two 16-byte FP32 accesses, 16-byte bf16).
- * Negative or unknown values: DOS_EINVAL. */
+/* Same, with an explicit launch shape.  The low four bits of `variant` pick the
+ * layout -- 0: each lane handles 4 consecutive elements per trip (16-byte FP32
+ * accesses, 8-byte bf16), two trips unrolled; 1: one trip; 2: four trips; 3: each
+ * lane handles 8 consecutive elements (two 16-byte FP32 accesses, 16-byte bf16);
+ * bit 4 (0x10) makes the loads non-temporal, bit 5 (0x20) the stores.
+ * dos_adam_step uses variant 0x31 with 64-thread blocks.  A NULL cfg means
+ * those defaults; unknown values: DOS_EINVAL. */
 dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
                              const dos_launch_cfg* cfg);
 
@@ -238,6 +240,12 @@ dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 /* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */
 dos_status dos_pinned_alloc(void** out, uint64_t bytes);
 dos_status dos_pinned_free(void* ptr);
+
+/* Measurement aid: a plain device-to-device copy kernel (reads `bytes`, writes
+ * `bytes`; multiple of 16; both pointers device memory, 16-byte aligned),
+ * asynchronous on hip_stream.  Hardware traffic counters read for this kernel
+ * give the scale of the same counters read for the AdamW kernel. */
+dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
 
 /* Reads one byte of every 4 KiB page of a host buffer with `threads` threads, so
  * that the first host update of a buffer that so far was only written by DMA does

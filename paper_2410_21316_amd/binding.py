@@ -91,6 +91,7 @@ SIGNATURES = {
     "dos_calibrate": (C.c_int, [C.c_void_p, C.POINTER(dos_cost_model)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
+    "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
     "dos_last_hip_error": (C.c_char_p, []),
@@ -251,6 +252,10 @@ def dos_pinned_alloc(nbytes: int) -> int:
 
 def dos_pinned_free(ptr: int) -> None:
     check(load().dos_pinned_free(C.c_void_p(ptr)), "dos_pinned_free")
+
+
+def dos_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    check(load().dos_probe_copy(C.c_void_p(dst), C.c_void_p(src), int(nbytes), C.c_void_p(stream)), "dos_probe_copy")
 
 
 def dos_host_prefault(ptr: int, nbytes: int, threads: int = 1) -> None:

@@ -193,6 +193,14 @@ __global__ __launch_bounds__(256) void pull_copy_kernel(u32x4* __restrict__ dst,
   if (blockIdx.x == 0 && t < n16) dst16[t] = src16[t];
 }
 
+// Plain device-to-device copy, 16 bytes per lane, one tile per block: the
+// known-size reference against which hardware traffic counters are scaled.
+__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                         uint64_t n_vec) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_vec) dst[i] = src[i];
+}
+
 template <bool NTL, bool NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, hipStream_t st_, float* p, float* m, float* v,
                          const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s) {
@@ -211,8 +219,10 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, hipStream_t st_, flo
 dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                        const AdamScalars& s, void* stream, const dos_launch_cfg* cfg) {
   if (n == 0) return DOS_OK;
-  int variant = cfg ? cfg->variant : 0;
-  int threads = (cfg && cfg->block_threads) ? cfg->block_threads : 256;
+  // Default shape (measured best on MI355X): one trip per lane, non-temporal loads
+  // and stores, one wave per block, one tile per block.
+  int variant = cfg ? cfg->variant : 0x31;
+  int threads = (cfg && cfg->block_threads) ? cfg->block_threads : 64;
   int64_t blocks = cfg ? cfg->grid_blocks : 0;
   if (variant < 0 || threads < 64 || threads > 512 || (threads % 64) != 0 || blocks < 0) return DOS_EINVAL;
   const int layout = variant & 0xF;
@@ -236,6 +246,21 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     note_hip_error((int)e, "launch of the fused AdamW kernel");
+    return DOS_EHIP;
+  }
+  return DOS_OK;
+}
+
+dos_status launch_probe_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+  const uint64_t n_vec = bytes >> 4;
+  if (n_vec == 0) return DOS_OK;
+  const uint64_t blocks = (n_vec + 255) / 256;
+  if (blocks > 0x7FFFFFFFull) return DOS_EINVAL;
+  hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                     reinterpret_cast<u32x4*>(dst), reinterpret_cast<const u32x4*>(src), n_vec);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    note_hip_error((int)e, "launch of the probe copy kernel");
     return DOS_EHIP;
   }
   return DOS_OK;

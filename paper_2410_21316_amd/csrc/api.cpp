@@ -63,6 +63,13 @@ dos_status dos_pinned_free(void* ptr) {
   return DOS_OK;
 }
 
+dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream) {
+  if (bytes == 0) return DOS_OK;
+  if (!dst_dev || !src_dev || (bytes & 15)) return DOS_EINVAL;
+  if (((uintptr_t)dst_dev | (uintptr_t)src_dev) & 15) return DOS_EALIGN;
+  return dos::launch_probe_copy(dst_dev, src_dev, bytes, hip_stream);
+}
+
 dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {
   if (!ptr && bytes) return DOS_EINVAL;
   if (bytes == 0) return DOS_OK;
