@@ -27,6 +27,18 @@ LINK_NOMINAL_GBPS = 64.0        # PCIe Gen5 x16 per direction, nominal
 BYTES_PER_PARAM = 28            # reads 4+4+4+2, writes 4+4+4+2
 
 
+def profiled_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (None if absent)."""
+    try:
+        with open(os.path.join(ROOT, "profiles", name)) as f:
+            for ln in f:
+                if ln.strip().startswith("traffic_bytes_per_launch"):
+                    return int(ln.split("=")[1].strip())
+    except OSError:
+        pass
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -134,7 +146,7 @@ def bench_c2(args, dos, torch, np):
         "hbm_GBps": BYTES_PER_PARAM * value / 1e9,
         "hbm_frac_of_peak": BYTES_PER_PARAM * value / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": profiled_traffic("adam_kernel_c2.md"),
                      "kernel": "dos::adam_kernel (fused AdamW)", "bytes_per_launch": BYTES_PER_PARAM * sizes[0],
                      "avg_launch_us": launch_s * 1e6},
     }
@@ -235,7 +247,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         sizes = list(state.sizes)
         log(f"[{tag}] pinned + filled {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
     # slots first (they decide what the context can do), then calibration, then the plan
-    probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 3e9)
+    probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
     plan = dos.dos_plan_subgroups(probe_cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
     ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE)
     if cm is None:
@@ -248,8 +260,12 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     if check:
         from oracle import adamw_oracle as ref
         idxs = [torch.from_numpy(W.sample_index(n)) for n in sizes]
-        samp = [[state.hp[i][idxs[i]].numpy().copy(), np.zeros(idxs[i].numel(), np.float32),
-                 np.zeros(idxs[i].numel(), np.float32), np.zeros(idxs[i].numel(), np.uint16)]
+
+        def take(t, idx):
+            return (t[idx.to(t.device)].cpu() if t.is_cuda else t[idx]).numpy().copy()
+
+        # the oracle's share starts from the state as it is now (wherever it lives)
+        samp = [[take(t, idxs[i]) for t in state.state(i)] + [np.zeros(idxs[i].numel(), np.uint16)]
                 for i in range(len(sizes))]
     for step in range(1, warmup + steps + 1):
         plan = dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
@@ -304,6 +320,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
            "host_threads": host_threads, "sample_mismatches_vs_oracle": mism, "steps": results}
     ctx.close()
+    ctx._keep[1].free()          # the pinned upload ring
     if own_state:
         state.free()
     return out
@@ -323,6 +340,53 @@ def bench_c4(args, dos, torch, np):
     return out
 
 
+def bench_c5(args, dos, torch, np):
+    """Interleaving sweep: subgroup size x GPU budget, heavy-tailed gradients with 5 % zeros, 3 steps per cell.
+    Each cell is run twice: state entirely host-resident (budget = staging only), and with the budget's
+    remainder used for static residents placed last."""
+    from paper_2410_21316_amd import workloads as W
+    import dos_synth as S
+    total_nominal = 13_000_000_000
+    cells = []
+    scale = None
+    for sg_params in (50_000_000, 100_000_000, 200_000_000, 400_000_000):
+        n_sg = -(-total_nominal // sg_params)
+        sizes = [sg_params] * (n_sg - 1) + [total_nominal - sg_params * (n_sg - 1)]
+        if scale is not None:                      # same parameter count for every subgroup size
+            keep = int(round(scale * total_nominal))
+            n_keep = max(1, keep // sg_params)
+            sizes = [sg_params] * n_keep
+        state = W.OffloadedState(sizes, S.BASE_SEED + 5, "cuda:0", pinned_reserve_bytes=1 << 30)
+        sizes = list(state.sizes)
+        if scale is None:
+            scale = sum(sizes) / total_nominal
+            log(f"[c5] this machine pins {sum(sizes)/1e9:.1f}B of the 13B parameters; budgets are scaled by {scale:.3f}")
+        cm = None
+        for budget_gb in (8, 16, 32, 64):
+            budget = int(budget_gb * 10**9 * scale)
+            for residents in (0, len(sizes)):
+                tag = f"c5 S={sg_params//10**6}M B={budget_gb}GB{' +res' if residents else ''}"
+                try:
+                    r = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=2,
+                                        host_threads=args.host_threads,
+                                        gkw=dict(heavy_tail=True, zero_pct=5.0), seed=S.BASE_SEED + 5,
+                                        check=True, tag=tag, state=state, residents_max=residents, cm=cm)
+                except dos.DosError as e:
+                    r = {"error": str(e)}
+                r.pop("steps", None)
+                r.update({"subgroup_params": sg_params, "budget_GB_nominal": budget_gb,
+                          "budget_bytes_scaled": budget, "static_residents": bool(residents)})
+                cells.append(r)
+        state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))   # residents back to the host
+        state.free()
+        del state
+        torch.cuda.empty_cache()
+    return {"workload": "c5: subgroup size {50,100,200,400}M x GPU budget {8,16,32,64} GB on host-resident state, "
+                        "grads Student-t(3) x 1e-3 with 5% zeros, 3 timed steps per cell; parameter count and "
+                        "budgets scaled by the fraction of 13B this machine can pin",
+            "scale": scale, "cells": cells}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -331,6 +395,7 @@ def main():
     ap.add_argument("--extra", default="c3,c4", help="comma list of extra workloads (c3, c4) or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also run the c5 subgroup-size x budget sweep")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (reference for traffic counters)")
     args = ap.parse_args()
@@ -354,6 +419,8 @@ def main():
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
     if "c4" in wanted:
         extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
+    if args.sweep:
+        extra["c5_interleaving_sweep"] = bench_c5(args, dos, torch, np)
     if extra:
         res["extra"] = extra
     print(json.dumps(res), flush=True)
