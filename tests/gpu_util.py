@@ -22,6 +22,8 @@ def assert_parity(tag, got_f32, want_f32, got_lp=None, want_lp=None, bitwise=Tru
     within 1 bf16 ULP; and (design goal) bit-identical."""
     for name, g, w in zip("pmv", got_f32, want_f32):
         g = np.asarray(g); w = np.asarray(w)
+        if g.shape == w.shape and np.array_equal(g.view(np.uint32), w.view(np.uint32)):
+            continue                      # bit-identical: both bars hold
         both_nan = np.isnan(g) & np.isnan(w)
         fin = ~both_nan
         with np.errstate(invalid="ignore", divide="ignore", over="ignore"):
@@ -37,6 +39,8 @@ def assert_parity(tag, got_f32, want_f32, got_lp=None, want_lp=None, bitwise=Tru
             assert nbad == 0, f"{tag}: {name} differs from the oracle in {nbad} of {g.size} bit patterns"
     if got_lp is not None:
         g = np.asarray(got_lp).view(np.uint16); w = np.asarray(want_lp).view(np.uint16)
+        if g.shape == w.shape and np.array_equal(g, w):
+            return
         nan = ((w & 0x7F80) == 0x7F80) & ((w & 0x7F) != 0)
         d = np.abs(ordered(g[~nan]) - ordered(w[~nan]))
         worst = int(d.max()) if d.size else 0

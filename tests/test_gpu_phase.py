@@ -137,11 +137,21 @@ def test_validation_errors_leave_state_untouched(hp):
 
 
 def test_transfers_overlap_full_duplex(hp):
-    """Prefetch of the next subgroup and flush of the previous one run at the
-    same time (Section 4.1); measured with the context's profiling events."""
+    """Prefetch of the next piece and flush of the previous one run at the same
+    time (Section 4.1); measured with the context's profiling events."""
+    from paper_2410_21316_amd import workloads as W
     sizes = [32 << 20] * 6
-    stats = run_phase_case(sizes, [1] * 6, None, 3, 16 << 20, hp, steps=2, grad_on_device=[1] * 6,
-                           flags=dos.DOS_CTX_PROFILE)
+    state = W.OffloadedState(sizes, S.BASE_SEED + 8)
+    ctx = W.make_context(3, 16 << 20, 4, flags=dos.DOS_CTX_PROFILE)
+    plan = dos.Plan.manual([1] * 6, None, 3, 16 << 20)
+    state.place([1] * 6)
+    try:
+        for step in (1, 2):
+            stats = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp))
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        state.free()
     assert stats.n_pieces == 12
     print({k: v for k, v in stats.asdict().items() if k.endswith("_s")})
     # a good part of the flush time runs concurrently with prefetches
