@@ -39,29 +39,28 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _bind(lib):
+    """Declare the C signatures on a loaded copy of the reference."""
+    f32p = ctypes.POINTER(ctypes.c_float)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    hp = [ctypes.c_float] * 5 + [ctypes.c_int64]
+    lib.ref_adamw_step.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64, *hp]
+    lib.ref_adamw_step.restype = ctypes.c_int
+    lib.ref_adamw_step_parallel.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64, *hp, ctypes.c_int]
+    lib.ref_adamw_step_parallel.restype = ctypes.c_int
+    lib.ref_adamw_scalars.argtypes = [*hp, f32p]
+    lib.ref_adamw_scalars.restype = None
+    lib.ref_bf16_to_f32_n.argtypes = [u16p, f32p, ctypes.c_uint64]
+    lib.ref_bf16_to_f32_n.restype = None
+    lib.ref_f32_to_bf16_n.argtypes = [f32p, u16p, ctypes.c_uint64]
+    lib.ref_f32_to_bf16_n.restype = None
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        f32p = ctypes.POINTER(ctypes.c_float)
-        u16p = ctypes.POINTER(ctypes.c_uint16)
-        hp = [ctypes.c_float] * 5 + [ctypes.c_int64]
-        lib.ref_adamw_step.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64, *hp]
-        lib.ref_adamw_step.restype = ctypes.c_int
-        lib.ref_adamw_step_parallel.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64, *hp,
-                                                ctypes.c_int]
-        lib.ref_adamw_step_parallel.restype = ctypes.c_int
-        lib.ref_adamw_scalars.argtypes = [*hp, f32p]
-        lib.ref_adamw_scalars.restype = None
-        lib.ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
-        lib.ref_bf16_to_f32.restype = ctypes.c_float
-        lib.ref_f32_to_bf16.argtypes = [ctypes.c_float]
-        lib.ref_f32_to_bf16.restype = ctypes.c_uint16
-        lib.ref_bf16_to_f32_n.argtypes = [u16p, f32p, ctypes.c_uint64]
-        lib.ref_bf16_to_f32_n.restype = None
-        lib.ref_f32_to_bf16_n.argtypes = [f32p, u16p, ctypes.c_uint64]
-        lib.ref_f32_to_bf16_n.restype = None
-        _lib = lib
+        _lib = _bind(ctypes.CDLL(build()))
     return _lib
 
 

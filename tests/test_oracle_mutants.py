@@ -1,0 +1,102 @@
+"""The pins must notice a plausible mistake anywhere in the oracle.  Each case
+plants one mistake in a copy of oracle/adamw_ref.c (on the CPU, in a temporary
+file), builds it, points the oracle's Python front end at the mutant and runs
+the pin checks: at least one of them has to fail."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import test_oracle_pins as pins
+from oracle import adamw_oracle as ref
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "adamw_ref.c")
+
+PIN_CHECKS = [
+    lambda: pins.test_first_step_is_sign_step(0.0),
+    lambda: pins.test_first_step_is_sign_step(0.3),
+    pins.test_zero_gradients_give_pure_decoupled_decay,
+    lambda: pins.test_constant_gradient_recurrences(3e-3),
+    lambda: pins.test_constant_gradient_recurrences(-7e-4),
+    lambda: pins.test_against_double_precision_textbook(1e-8, 0.01, 1e-4),
+    lambda: pins.test_against_double_precision_textbook(1e-3, 0.0, 1e-2),
+    lambda: pins.test_against_double_precision_textbook(1e-5, 0.2, 3e-3),
+    pins.test_eps_sits_outside_the_root_and_is_not_bias_corrected,
+    pins.test_against_torch_adamw,
+    pins.test_elements_are_independent_brute_force,
+    pins.test_parallel_loop_is_bit_identical_to_scalar_loop,
+    pins.test_step_scalars_match_their_definitions,
+    pins.test_bf16_widening_is_exact_and_roundtrips_exhaustively,
+    pins.test_bf16_rounding_hand_built_cases,
+    pins.test_bf16_rounding_is_nearest_value_with_even_ties,
+]
+
+# (name, [(text in the reference, planted replacement), ...])
+MUTANTS = [
+    ("beta2 used for the first moment", [("float a = s->beta1 * *m;", "float a = s->beta2 * *m;")]),
+    ("first moment terms subtracted", [("float mt = a + b;", "float mt = a - b;")]),
+    ("gradient not squared", [("float f = e * g;", "float f = e;")]),
+    ("second moment terms subtracted", [("float vt = c + f;", "float vt = c - f;")]),
+    ("square root dropped", [("float r = sqrtf(vt);", "float r = vt;")]),
+    ("eps dropped", [("float d = q + s->eps;", "float d = q;")]),
+    ("eps inside the root", [("float r = sqrtf(vt);", "float r = sqrtf(vt + s->eps);"),
+                             ("float d = q + s->eps;", "float d = q;")]),
+    ("second bias correction dropped", [("float q = r * s->inv_sqrt_bc2;", "float q = r;")]),
+    ("second bias correction inverted", [("s.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));",
+                                          "s.inv_sqrt_bc2 = (float)(sqrt(bc2));")]),
+    ("first bias correction dropped", [("s.step_size = (float)((double)lr / bc1);",
+                                        "s.step_size = (float)((double)lr);")]),
+    ("bias corrections use the wrong beta", [("double bc2 = 1.0 - pow((double)beta2, (double)step);",
+                                              "double bc2 = 1.0 - pow((double)beta1, (double)step);")]),
+    ("step counted from zero", [("double bc1 = 1.0 - pow((double)beta1, (double)step);",
+                                 "double bc1 = 1.0 - pow((double)beta1, (double)step + 1.0);")]),
+    ("weight decay dropped", [("float pd = *p * s->decay;", "float pd = *p;")]),
+    ("decay without the learning rate", [("s.decay = (float)(1.0 - (double)lr * (double)weight_decay);",
+                                          "s.decay = (float)(1.0 - (double)weight_decay);")]),
+    ("decay applied after the step", [("float pt = pd - w;", "float pt = (*p - w) * s->decay;")]),
+    ("update added instead of subtracted", [("float pt = pd - w;", "float pt = pd + w;")]),
+    ("quotient transposed", [("float u = mt / d;", "float u = d / mt;")]),
+    ("old momentum in the update", [("float u = mt / d;", "float u = *m / d;")]),
+    ("one minus beta1 replaced by beta1", [("s.omb1 = 1.0f - beta1;", "s.omb1 = beta1;")]),
+    ("one minus beta2 replaced by one minus beta1", [("s.omb2 = 1.0f - beta2;", "s.omb2 = 1.0f - beta1;")]),
+    ("gradient index reversed", [("ref_adamw_element(&s, &p[i], &m[i], &v[i], g[i], &p_lp[i]);\n  return 0;",
+                                  "ref_adamw_element(&s, &p[i], &m[i], &v[i], g[n - 1 - i], &p_lp[i]);\n  return 0;")]),
+    ("state arrays swapped", [("ref_adamw_element(&s, &p[i], &m[i], &v[i], g[i], &p_lp[i]);\n  return 0;",
+                               "ref_adamw_element(&s, &p[i], &v[i], &m[i], g[i], &p_lp[i]);\n  return 0;")]),
+    ("bf16 widening shifted wrongly", [("uint32_t u = (uint32_t)h << 16;", "uint32_t u = (uint32_t)h << 15;")]),
+    ("bf16 rounding truncates", [("keep += 1u;", "keep += 0u;")]),
+    ("bf16 ties round up", [("if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1u;",
+                             "if (rest >= 0x8000u) keep += 1u;")]),
+    ("bf16 NaN not kept", [("if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);", "")]),
+    ("low-precision copy of the old parameter", [("*p_lp = ref_f32_to_bf16(pt);", "*p_lp = ref_f32_to_bf16(pd);")]),
+    ("parallel loop skips the last element", [("for (int64_t i = 0; i < (int64_t)n; ++i)",
+                                               "for (int64_t i = 0; i < (int64_t)n - 1; ++i)")]),
+]
+
+
+@pytest.mark.parametrize("name,edits", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(name, edits, tmp_path, monkeypatch):
+    text = open(SRC).read()
+    for old, new in edits:
+        assert text.count(old) >= 1, f"reference text changed: {old!r}"
+        text = text.replace(old, new, 1)
+    c_file = tmp_path / "mutant.c"
+    c_file.write_text(text)
+    so = tmp_path / "libmutant.so"
+    subprocess.check_call(["gcc", *ref.CFLAGS, str(c_file), "-o", str(so), "-lm"])
+    ref._load()                                           # make sure the real one is built and bound
+    monkeypatch.setattr(ref, "_lib", ref._bind(ctypes.CDLL(str(so))))
+    failed = []
+    for check in PIN_CHECKS:
+        try:
+            check()
+        except AssertionError:
+            failed.append(check)
+            break
+    assert failed, f"no pin noticed: {name}"
+
+
+def test_unmodified_reference_passes_every_pin():
+    for check in PIN_CHECKS:
+        check()
