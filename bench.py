@@ -230,8 +230,27 @@ def bench_c3(args, dos, torch, np):
     return out
 
 
+def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max):
+    """schedule: 'balanced' (this library's planner), 'stride' (Eq. 1 + Algorithm 1), 'all_cpu' (every update
+    on the host cores, as a fully offloaded optimizer does), 'static' (a fixed set of residents that fits the
+    budget, everything else on the host cores: static hybrid placement without interleaving)."""
+    if schedule == "balanced":
+        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
+    if schedule == "stride":
+        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_STRIDE, residents_max)
+    base = dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED,
+                                  len(sizes) if schedule == "static" else 0)
+    if schedule == "all_cpu":
+        return dos.Plan.manual([dos.DOS_ON_CPU] * len(sizes), None, base.c.n_slots, base.c.slot_params)
+    if schedule == "static":
+        res = base.residents
+        return dos.Plan.manual([dos.DOS_ON_GPU if r else dos.DOS_ON_CPU for r in res], None, base.c.n_slots,
+                               base.c.slot_params, res)
+    raise ValueError(schedule)
+
+
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
-                    cm=None, residents_max=0, tag="c4", state=None, adapt=True):
+                    cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced"):
     """Plan + run the interleaved phase on a host-offloaded state; returns a dict."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
@@ -268,7 +287,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         samp = [[take(t, idxs[i]) for t in state.state(i)] + [np.zeros(idxs[i].numel(), np.uint16)]
                 for i in range(len(sizes))]
     for step in range(1, warmup + steps + 1):
-        plan = dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
+        plan = make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max)
         state.place(plan.targets, plan.residents)
         state.fill_grads(step, **gkw)
         state.sync_host_grads()
@@ -287,11 +306,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         if adapt:
             # feed the measured lane rates back into the cost model (the plan is
             # re-derived every iteration, as a training loop would)
-            if st.params_cpu and st.cpu_lane_s > 0:
-                cm.cpu_params_per_s = st.params_cpu / st.cpu_lane_s
-            if st.params_gpu and st.h2d_busy_s > 0 and st.d2h_busy_s > 0:
-                cm.h2d_Bps = 12.0 * st.params_gpu / st.h2d_busy_s
-                cm.d2h_Bps = 12.0 * st.params_gpu / st.d2h_busy_s
+            dos.dos_cost_model_observe(cm, st)
         if check:
             for i in range(len(sizes)):
                 gs = state.g[i][idxs[i].to("cuda:0")].view(torch.int16).cpu().numpy().view(np.uint16)
@@ -338,6 +353,38 @@ def bench_c4(args, dos, torch, np):
                             "the machine's pinned-host-memory limit; same subgroup size, budget and schedule")
         out["extrapolated_13b_s_per_iter"] = 13e9 / out["params_per_s"]
     return out
+
+
+def bench_ablation(args, dos, torch, np):
+    """The same host-offloaded state under different schedules, all through dos_run_update_phase."""
+    from paper_2410_21316_amd import workloads as W
+    import dos_synth as S
+    sizes = [100_000_000] * 130
+    state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30)
+    sizes = list(state.sizes)
+    scale = sum(sizes) / 13e9
+    budget = int(40 * 10**9 * scale)
+    rows = []
+    for name, schedule, res in (("all updates on host cores (fully offloaded optimizer)", "all_cpu", 0),
+                                ("static residents only (fixed hybrid placement)", "static", len(sizes)),
+                                ("stride from Eq. 1 + Algorithm 1 placement", "stride", 0),
+                                ("balanced plan with feedback (default)", "balanced", 0),
+                                ("balanced plan + static residents placed last", "balanced", len(sizes))):
+        r = run_interleaved(dos, torch, np, sizes, budget, steps=4, warmup=3, host_threads=args.host_threads, gkw={},
+                            seed=S.BASE_SEED + 4, check=True, tag="abl " + schedule + ("+res" if res else ""),
+                            state=state, residents_max=res, schedule=schedule)
+        last = r.pop("steps")[-1]
+        rows.append({"schedule": name, "s_per_iter": r["update_phase_s_per_iter"], "best_s": r["best_s"],
+                     "params_per_s": r["params_per_s"], "n_gpu": last["n_gpu"], "n_cpu": last["n_cpu"],
+                     "n_resident": last["n_resident"], "sample_mismatches_vs_oracle": r["sample_mismatches_vs_oracle"]})
+    state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
+    state.free()
+    base = rows[0]["s_per_iter"]
+    for r in rows:
+        r["speedup_vs_all_cpu"] = base / r["s_per_iter"]
+    return {"workload": f"{len(sizes)} x 100M-parameter subgroups in pinned host memory, GPU budget "
+                        f"{budget/1e9:.1f} GB (40 GB scaled by {scale:.3f}), grads ~N(0,1e-3), 4 timed steps",
+            "rows": rows}
 
 
 def bench_c5(args, dos, torch, np):
@@ -395,6 +442,7 @@ def main():
     ap.add_argument("--extra", default="c3,c4", help="comma list of extra workloads (c3, c4) or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
     ap.add_argument("--sweep", action="store_true", help="also run the c5 subgroup-size x budget sweep")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (reference for traffic counters)")
@@ -419,6 +467,8 @@ def main():
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
     if "c4" in wanted:
         extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
+    if args.ablation:
+        extra["schedule_ablation"] = bench_ablation(args, dos, torch, np)
     if args.sweep:
         extra["c5_interleaving_sweep"] = bench_c5(args, dos, torch, np)
     if extra:

@@ -235,6 +235,13 @@ dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, c
  * the device kernel over one slot, the host update over the upload ring. */
 dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 
+/* Replaces the host-update rate and the link rates of `cm` by what the phase that
+ * produced `st` actually reached (host lane: parameters / lane time; link: bytes /
+ * summed copy time when the context profiles, else bytes / lane time as an upper
+ * bound on the time).  Call it after every phase and re-plan: the plan then
+ * tracks contention between the two lanes. */
+dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st);
+
 /* ---- utilities ------------------------------------------------------------ */
 
 /* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */

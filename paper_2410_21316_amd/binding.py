@@ -89,6 +89,7 @@ SIGNATURES = {
                                        C.POINTER(dos_plan), C.POINTER(dos_hparams),
                                        C.POINTER(dos_phase_stats)]),
     "dos_calibrate": (C.c_int, [C.c_void_p, C.POINTER(dos_cost_model)]),
+    "dos_cost_model_observe": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(dos_phase_stats)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
     "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
@@ -242,6 +243,10 @@ def dos_plan_cost(cm: dos_cost_model, sizes, targets, n_slots: int, residents=No
                                C.byref(low)),
           "dos_plan_cost")
     return pred.value, low.value
+
+
+def dos_cost_model_observe(cm: dos_cost_model, st: dos_phase_stats) -> None:
+    check(load().dos_cost_model_observe(C.byref(cm), C.byref(st)), "dos_cost_model_observe")
 
 
 def dos_pinned_alloc(nbytes: int) -> int:

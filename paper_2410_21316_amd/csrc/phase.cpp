@@ -688,20 +688,27 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f};
     const int T = c->T;
     const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
-    auto run = [&] {
+    // every thread sweeps its own slice `reps` times; the threads are started once
+    auto run = [&](int reps) {
       std::vector<std::thread> th;
       for (int t = 0; t < T; ++t) {
         const uint64_t lo = (uint64_t)t * per;
         if (lo >= n) break;
         const uint64_t cnt = std::min(per, n - lo);
-        th.emplace_back([=] { dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc); });
+        th.emplace_back([=] {
+          for (int r = 0; r < reps; ++r) dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc);
+        });
       }
       for (auto& t : th) t.join();
     };
-    run();
-    const auto a = clk::now();
-    const int hreps = 3;
-    for (int r = 0; r < hreps; ++r) run();
+    run(1);
+    auto a = clk::now();
+    run(2);
+    const double t2 = secs(a, clk::now());
+    // aim at ~0.2 s of measured work
+    const int hreps = (int)std::max(2.0, std::min(400.0, 0.2 / (t2 / 2.0)));
+    a = clk::now();
+    run(hreps);
     out->cpu_params_per_s = (double)n * hreps / secs(a, clk::now());
   }
   out->downscale_params_per_s = 0.0;

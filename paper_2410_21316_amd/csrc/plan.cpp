@@ -220,3 +220,24 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   }
   return DOS_OK;
 }
+
+// Feeds one phase's measured lane rates back into the cost model, so that the
+// next plan balances the lanes as they really ran (host DRAM contention between
+// the host update and the DMA traffic makes both slower than when calibrated
+// alone -- the paper observes the same in its CPU-cores-per-GPU study, Section 5.4).
+extern "C" dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st) {
+  if (!cm || !st) return DOS_EINVAL;
+  if (st->params_cpu > 0 && st->cpu_lane_s > 0.0) cm->cpu_params_per_s = (double)st->params_cpu / st->cpu_lane_s;
+  if (st->params_gpu > 0 && st->h2d_busy_s > 0.0 && st->d2h_busy_s > 0.0) {
+    // summed copy durations (DOS_CTX_PROFILE) give the rate each direction reached while busy
+    const double staged = st->h2d_bytes - 2.0 * (double)st->params_cpu;  // bytes the prefetches moved
+    cm->h2d_Bps = staged / st->h2d_busy_s;
+    cm->d2h_Bps = st->d2h_bytes / st->d2h_busy_s;
+  } else if (st->params_gpu > 0 && st->gpu_lane_s > 0.0 && st->d2h_bytes > 0.0) {
+    // without per-copy timing: the lane as a whole bounds both directions
+    const double rate = st->d2h_bytes / st->gpu_lane_s;
+    if (rate < cm->d2h_Bps) cm->d2h_Bps = rate;
+    if (rate < cm->h2d_Bps) cm->h2d_Bps = rate;
+  }
+  return DOS_OK;
+}

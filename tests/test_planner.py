@@ -208,3 +208,29 @@ def test_planner_is_deterministic():
     a = dos.dos_plan_subgroups(cm, sizes, 16 * 10**9)
     b = dos.dos_plan_subgroups(cm, sizes, 16 * 10**9)
     assert a.targets == b.targets and a.c.predicted_s == b.c.predicted_s
+
+
+def test_cost_model_observe_takes_the_measured_rates():
+    cm = dos.cost_model(56e9, 48e9, 200e9, 8e9)
+    st = dos.dos_phase_stats()
+    st.params_cpu, st.cpu_lane_s = 3_600_000_000, 0.45
+    st.params_gpu = 1_300_000_000
+    st.h2d_bytes = 12.0 * st.params_gpu + 2.0 * st.params_cpu
+    st.d2h_bytes = 12.0 * st.params_gpu
+    st.h2d_busy_s, st.d2h_busy_s, st.gpu_lane_s = 0.40, 0.43, 0.46
+    dos.dos_cost_model_observe(cm, st)
+    assert cm.cpu_params_per_s == pytest.approx(8e9)
+    assert cm.h2d_Bps == pytest.approx(12.0 * 1.3e9 / 0.40)
+    assert cm.d2h_Bps == pytest.approx(12.0 * 1.3e9 / 0.43)
+    assert cm.gpu_params_per_s == 200e9
+    # without per-copy timing only an upper bound on the time is known: rates may only drop
+    cm2 = dos.cost_model(56e9, 48e9, 200e9, 8e9)
+    st.h2d_busy_s = st.d2h_busy_s = -1.0
+    dos.dos_cost_model_observe(cm2, st)
+    assert cm2.d2h_Bps == pytest.approx(12.0 * 1.3e9 / 0.46) and cm2.h2d_Bps == pytest.approx(12.0 * 1.3e9 / 0.46)
+    # nothing measured on a lane: that lane's rate stays
+    cm3 = dos.cost_model(56e9, 48e9, 200e9, 8e9)
+    dos.dos_cost_model_observe(cm3, dos.dos_phase_stats())
+    assert (cm3.h2d_Bps, cm3.d2h_Bps, cm3.cpu_params_per_s) == (56e9, 48e9, 8e9)
+    lib = dos.load()
+    assert lib.dos_cost_model_observe(None, C.byref(st)) == dos.DOS_EINVAL
