@@ -250,8 +250,10 @@ def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max):
 
 
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
-                    cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced"):
-    """Plan + run the interleaved phase on a host-offloaded state; returns a dict."""
+                    cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced",
+                    fresh_grads=True):
+    """Plan + run the interleaved phase on a host-offloaded state; returns a dict.
+    fresh_grads=False generates the gradients once and reuses them for every step."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     hp_kw = dict(S.HPARAMS)
@@ -274,6 +276,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
             f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (ring-sized, optimistic)")
     link = (cm.h2d_Bps, cm.d2h_Bps)
+    calibrated = (cm.h2d_Bps, cm.d2h_Bps, cm.gpu_params_per_s, cm.cpu_params_per_s, cm.downscale_params_per_s,
+                  cm.launch_overhead_s)
     results = []
     samp = None
     if check:
@@ -289,7 +293,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     for step in range(1, warmup + steps + 1):
         plan = make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max)
         state.place(plan.targets, plan.residents)
-        state.fill_grads(step, **gkw)
+        if fresh_grads or step == 1:
+            state.fill_grads(step, **gkw)
         state.sync_host_grads()
         st = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp_kw))
         lb_plan = max(st.h2d_bytes / link[0], st.d2h_bytes / link[1])
@@ -333,7 +338,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
            "h2d_frac_of_measured_link": best["h2d_GBps"] * 1e9 / link[0],
            "d2h_frac_of_measured_link": best["d2h_GBps"] * 1e9 / link[1],
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
-           "host_threads": host_threads, "sample_mismatches_vs_oracle": mism, "steps": results}
+           "host_threads": host_threads, "sample_mismatches_vs_oracle": mism, "steps": results,
+           "calibrated": calibrated}
     ctx.close()
     ctx._keep[1].free()          # the pinned upload ring
     if own_state:
@@ -417,10 +423,14 @@ def bench_c5(args, dos, torch, np):
                     r = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=2,
                                         host_threads=args.host_threads,
                                         gkw=dict(heavy_tail=True, zero_pct=5.0), seed=S.BASE_SEED + 5,
-                                        check=True, tag=tag, state=state, residents_max=residents, cm=cm)
+                                        check=True, tag=tag, state=state, residents_max=residents,
+                                        cm=(dos.cost_model(*cm) if cm else None), fresh_grads=False)
+                    if cm is None:
+                        cm = r.get("calibrated")
                 except dos.DosError as e:
                     r = {"error": str(e)}
                 r.pop("steps", None)
+                r.pop("calibrated", None)
                 r.update({"subgroup_params": sg_params, "budget_GB_nominal": budget_gb,
                           "budget_bytes_scaled": budget, "static_residents": bool(residents)})
                 cells.append(r)
