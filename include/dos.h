@@ -183,9 +183,13 @@ typedef struct dos_ctx_config {
   void* slot_mem;          /* device memory for the staging ring (caller allocates)   */
   uint64_t slot_bytes;     /* its size                                                */
   uint64_t slot_params;    /* capacity of one slot in parameters                      */
-  int32_t n_slots;         /* slots to use; n_slots*14*slot_params <= slot_bytes      */
+  int32_t n_slots;         /* slots to use (<= 16); each takes 12*slot_params bytes of
+                              slot_mem, or 14*slot_params if that fits (then host-
+                              resident gradients of GPU-planned subgroups are staged) */
   int32_t host_threads;    /* worker threads for CPU-planned subgroups (>= 1)         */
-  void* h2d_stream;        /* hipStream_t for prefetches, NULL = library creates one  */
+  void* h2d_stream;        /* hipStream_t for prefetches; NULL (for any of the four) =
+                              the library's own stream for that role, created once per
+                              device and kept until the process ends                  */
   void* compute_stream;    /* hipStream_t for kernels                                 */
   void* d2h_stream;        /* hipStream_t for flushes                                 */
   void* upload_stream;     /* hipStream_t for 16-bit parameter uploads                */

@@ -72,7 +72,7 @@ struct dos_ctx {
   std::vector<std::atomic<int64_t>> ring_seq;  // last chunk index recorded on each ring entry
   // profiling events
   std::vector<hipEvent_t> prof;  // 6 per piece
-  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipEvent_t t0 = nullptr;  // start of the phase on the H2D stream (origin of the profile timeline)
   // host workers
   int T = 1;
   std::vector<std::thread> workers;
@@ -101,9 +101,10 @@ struct dos_ctx {
 namespace {
 
 // Streams the library creates are created once per device and kept until the
-// process ends: on this platform a copy stream that is destroyed and created
-// again can end up sharing a DMA engine with the stream of the other direction
-// (prefetches and flushes then serialise); the first set does not.
+// process ends.  Measured on MI355X / ROCm 7: after the copy streams of a context
+// had been destroyed and new ones created, prefetches and flushes of every later
+// context ran strictly one after the other (no duplex overlap) for the rest of
+// the process; streams that are never destroyed keep both directions concurrent.
 struct DeviceStreams {
   hipStream_t s[4] = {nullptr, nullptr, nullptr, nullptr};
   bool made = false;
@@ -222,7 +223,6 @@ void destroy(dos_ctx* c) {
   for (auto e : c->prof)
     if (e) (void)hipEventDestroy(e);
   if (c->t0) (void)hipEventDestroy(c->t0);
-  if (c->t1) (void)hipEventDestroy(c->t1);
   delete c;
 }
 
@@ -314,7 +314,6 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
   for (int r = 0; r < ring_n; ++r)
     if ((e = hipEventCreateWithFlags(&c->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
   if ((e = hipEventCreate(&c->t0)) != hipSuccess) return fail(e, "hipEventCreate");
-  if ((e = hipEventCreate(&c->t1)) != hipSuccess) return fail(e, "hipEventCreate");
   if (c->flags & DOS_CTX_PROFILE) {
     c->prof.assign((size_t)kProfPieces * 6, nullptr);
     for (auto& ev : c->prof)
