@@ -122,3 +122,77 @@ def test_interleaved_phase_on_100m_subgroups_sampled(heavy, hp):
         ctx.close()
         ctx._keep[1].free()
         state.free()
+
+
+def test_subgroup_larger_than_32_bit_indices(hp):
+    """One device-resident subgroup of 2^31 + 4099 parameters: element indices do
+    not fit 32 bits and byte offsets pass 2^33.  The oracle owns three windows:
+    the start, the stretch across element 2^31, and the ragged end."""
+    n = (1 << 31) + 4099
+    free, _ = torch.cuda.mem_get_info()
+    if free < 16 * n + (8 << 30):
+        pytest.skip("needs 40 GB of free device memory")
+    seed = S.BASE_SEED + 31
+    state = W.ResidentState([n], seed, DEV)
+    windows = [(0, 70_000), ((1 << 31) - 35_000, 39_000), (n - 70_003, 70_003),
+               ((1 << 30) - 1000, 2000), (3 * (1 << 29) - 1000, 2000)]
+    want = [[state.p[0][a:a + c].cpu().numpy(), np.zeros(c, np.float32), np.zeros(c, np.float32),
+             np.zeros(c, np.uint16)] for a, c in windows]
+    stream = torch.cuda.current_stream().cuda_stream
+    for step in (1, 2):
+        state.fill_grads(0, step, zero_pct=1.0)
+        dos.dos_adam_step(state.descs[0][0], dos.hparams(step=step, **hp), stream)
+        torch.cuda.synchronize()
+        for (a, c), w in zip(windows, want):
+            ref.adamw_step(w[0], w[1], w[2], bits(state.g[0][0][a:a + c]), w[3], step=step, **hp)
+    for (a, c), w in zip(windows, want):
+        got = tuple(t[a:a + c].cpu().numpy() for t in (state.p[0], state.m[0], state.v[0]))
+        assert_parity(f"window at {a}", got, w[:3], bits(state.lp[0][a:a + c]), w[3])
+    # every element was visited exactly once per step: v > 0 wherever g was non-zero in step 2
+    untouched = int(((state.v[0] == 0) & (state.g[0][0] != 0)).sum())
+    assert untouched == 0
+
+
+def test_interleaved_phase_with_arrays_over_4_gib(hp):
+    """Two subgroups of 2^30 + 5 parameters (each FP32 array is over 4 GiB): one
+    streamed through the GPU in pieces, one updated by the host cores in chunks;
+    sampled oracle plus the ragged tails."""
+    n = (1 << 30) + 5
+    sizes = [n, n]
+    seed = S.BASE_SEED + 32
+    state = W.OffloadedState(sizes, seed, DEV)
+    if state.truncated:
+        state.free()
+        pytest.skip("cannot pin 30 GB of host memory here")
+    threads = len(os.sched_getaffinity(0))
+    plan = dos.Plan.manual([1, 0], None, 3, 16 << 20)
+    ctx = W.make_context(3, 16 << 20, threads)
+    idxs = [torch.from_numpy(np.concatenate([W.sample_index(n, every=1 << 24, take=1 << 14),
+                                             np.arange(n - 4099, n, dtype=np.int64),
+                                             np.arange((1 << 30) - 2048, (1 << 30) + 5, dtype=np.int64)]))
+            for _ in sizes]
+    idxs = [torch.unique(ix) for ix in idxs]
+    want = [[state.hp[i][idxs[i]].numpy().copy(), np.zeros(idxs[i].numel(), np.float32),
+             np.zeros(idxs[i].numel(), np.float32), np.zeros(idxs[i].numel(), np.uint16)] for i in range(2)]
+    try:
+        for step in (1, 2):
+            state.place(plan.targets, plan.residents)
+            state.fill_grads(step)
+            state.sync_host_grads()
+            st = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp))
+            assert st.params_gpu == n and st.params_cpu == n
+            assert st.n_pieces == -(-n // (16 << 20))
+            for i in range(2):
+                g = bits(state.g[i][idxs[i].to(DEV)])
+                ref.adamw_step(want[i][0], want[i][1], want[i][2], g, want[i][3], step=step, threads=0, **hp)
+        for i in range(2):
+            got = tuple(t[idxs[i]].numpy() for t in (state.hp[i], state.hm[i], state.hv[i]))
+            assert_parity(f"big subgroup {i}", got, want[i][:3], bits(state.lp[i][idxs[i].to(DEV)]), want[i][3])
+            # no element skipped: v > 0 wherever the last gradient was non-zero
+            v_dev = state.hv[i].to(DEV)
+            assert int(((v_dev == 0) & (state.g[i] != 0)).sum()) == 0
+            del v_dev
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        state.free()
