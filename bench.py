@@ -234,16 +234,16 @@ def bench_c3(args, dos, torch, np):
     return out
 
 
-def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max):
+def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp=12):
     """schedule: 'balanced' (this library's planner), 'stride' (Eq. 1 + Algorithm 1), 'all_cpu' (every update
     on the host cores, as a fully offloaded optimizer does), 'static' (a fixed set of residents that fits the
     budget, everything else on the host cores: static hybrid placement without interleaving)."""
     if schedule == "balanced":
-        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
+        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max, bpp)
     if schedule == "stride":
-        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_STRIDE, residents_max)
+        return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_STRIDE, residents_max, bpp)
     base = dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED,
-                                  len(sizes) if schedule == "static" else 0)
+                                  len(sizes) if schedule == "static" else 0, bpp)
     if schedule == "all_cpu":
         return dos.Plan.manual([dos.DOS_ON_CPU] * len(sizes), None, base.c.n_slots, base.c.slot_params)
     if schedule == "static":
@@ -255,9 +255,11 @@ def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max):
 
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
                     cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced",
-                    fresh_grads=True):
+                    fresh_grads=True, spill_grads=False):
     """Plan + run the interleaved phase on a host-offloaded state; returns a dict.
-    fresh_grads=False generates the gradients once and reuses them for every step."""
+    fresh_grads=False generates the gradients once and reuses them for every step;
+    spill_grads=True keeps every gradient in pinned host memory (GPU-planned subgroups fetch theirs
+    with p, m, v through 14-byte slots)."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     hp_kw = dict(S.HPARAMS)
@@ -273,8 +275,10 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         log(f"[{tag}] pinned + filled {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
     # slots first (they decide what the context can do), then calibration, then the plan
     probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
-    plan = dos.dos_plan_subgroups(probe_cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max)
-    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE)
+    bpp = 14 if spill_grads else 12
+    plan = dos.dos_plan_subgroups(probe_cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max, bpp)
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE,
+                         stage_grads=spill_grads)
     if cm is None:
         cm = ctx.dos_calibrate()
         log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
@@ -295,8 +299,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         samp = [[take(t, idxs[i]) for t in state.state(i)] + [np.zeros(idxs[i].numel(), np.uint16)]
                 for i in range(len(sizes))]
     for step in range(1, warmup + steps + 1):
-        plan = make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max)
-        state.place(plan.targets, plan.residents)
+        plan = make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp)
+        state.place(plan.targets, plan.residents, spill_all_grads=spill_grads)
         if fresh_grads or step == 1:
             state.fill_grads(step, **gkw)
         state.sync_host_grads()
@@ -375,26 +379,46 @@ def bench_ablation(args, dos, torch, np):
     scale = sum(sizes) / 13e9
     budget = int(40 * 10**9 * scale)
     rows = []
-    for name, schedule, res in (("all updates on host cores (fully offloaded optimizer)", "all_cpu", 0),
-                                ("static residents only (fixed hybrid placement)", "static", len(sizes)),
-                                ("stride from Eq. 1 + Algorithm 1 placement", "stride", 0),
-                                ("balanced plan with feedback (default)", "balanced", 0),
-                                ("balanced plan + static residents placed last", "balanced", len(sizes))):
+    for name, schedule, res, spill in (
+            ("all updates on host cores (fully offloaded optimizer)", "all_cpu", 0, False),
+            ("static residents only (fixed hybrid placement)", "static", len(sizes), False),
+            ("stride from Eq. 1 + Algorithm 1 placement", "stride", 0, False),
+            ("balanced plan with feedback (default)", "balanced", 0, False),
+            ("balanced plan, all gradients spilled to the host and fetched with the state", "balanced", 0, True),
+            ("balanced plan + static residents placed last", "balanced", len(sizes), False)):
         r = run_interleaved(dos, torch, np, sizes, budget, steps=4, warmup=3, host_threads=args.host_threads, gkw={},
-                            seed=S.BASE_SEED + 4, check=True, tag="abl " + schedule + ("+res" if res else ""),
-                            state=state, residents_max=res, schedule=schedule)
+                            seed=S.BASE_SEED + 4, check=True,
+                            tag="abl " + schedule + ("+res" if res else "") + ("+spill" if spill else ""),
+                            state=state, residents_max=res, schedule=schedule, spill_grads=spill)
         last = r.pop("steps")[-1]
         rows.append({"schedule": name, "s_per_iter": r["update_phase_s_per_iter"], "best_s": r["best_s"],
                      "params_per_s": r["params_per_s"], "n_gpu": last["n_gpu"], "n_cpu": last["n_cpu"],
                      "n_resident": last["n_resident"], "sample_mismatches_vs_oracle": r["sample_mismatches_vs_oracle"]})
-    state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
-    state.free()
     base = rows[0]["s_per_iter"]
     for r in rows:
         r["speedup_vs_all_cpu"] = base / r["s_per_iter"]
+    # host cores per GPU (the paper's CPU-cores-per-GPU study, Section 5.4): fewer host threads make the
+    # all-CPU schedule slower and the interleaved one comparatively better
+    thread_rows = []
+    for T in sorted({2, 4, 8, 12, args.host_threads}):
+        if T > args.host_threads:
+            continue
+        pair = {}
+        for schedule in ("all_cpu", "balanced"):
+            r = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=3, host_threads=T, gkw={},
+                                seed=S.BASE_SEED + 4, check=False, tag=f"threads {T} {schedule}", state=state,
+                                schedule=schedule, fresh_grads=False)
+            pair[schedule] = r
+        thread_rows.append({"host_threads": T, "all_cpu_s": pair["all_cpu"]["update_phase_s_per_iter"],
+                            "balanced_s": pair["balanced"]["update_phase_s_per_iter"],
+                            "gpu_fraction": pair["balanced"]["gpu_fraction"],
+                            "speedup": pair["all_cpu"]["update_phase_s_per_iter"]
+                            / pair["balanced"]["update_phase_s_per_iter"]})
+    state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
+    state.free()
     return {"workload": f"{len(sizes)} x 100M-parameter subgroups in pinned host memory, GPU budget "
                         f"{budget/1e9:.1f} GB (40 GB scaled by {scale:.3f}), grads ~N(0,1e-3), 4 timed steps",
-            "rows": rows}
+            "rows": rows, "host_threads_sweep": thread_rows}
 
 
 def bench_c5(args, dos, torch, np):

@@ -118,6 +118,7 @@ class OffloadedState:
                 dos.dos_host_prefault(blk.ptr, blk.nbytes, 16)
         del zeros, tmp
         self.targets = [dos.DOS_ON_CPU] * n_sg
+        self.grads_on_host = [True] * n_sg
         self.sgs = None
 
     def fill_grads(self, step: int, scales=None, **gkw):
@@ -128,8 +129,11 @@ class OffloadedState:
             S.fill_chunked(lambda start, count: S.grads_bf16(self.seed, step, i, start, count, self.device,
                                                              scale=sc, **gkw), self.g[i])
 
-    def place(self, targets, residents=None):
-        """Build the descriptor array for a plan; move resident state as needed."""
+    def place(self, targets, residents=None, spill_all_grads=False):
+        """Build the descriptor array for a plan; move resident state as needed.
+        spill_all_grads: gradients of GPU-planned (non-resident) subgroups live in
+        pinned host memory too and are fetched with p, m, v (Section 4.1, the case
+        where freed GPU memory cannot hold them)."""
         n_sg = len(self.sizes)
         residents = residents if residents is not None else [0] * n_sg
         arr = (dos.dos_subgroup * max(n_sg, 1))()
@@ -141,20 +145,22 @@ class OffloadedState:
                     h.copy_(d)
                 self.res[i] = None
             st = self.res[i] if residents[i] else (self.hp[i], self.hm[i], self.hv[i])
-            on_gpu = targets[i] == dos.DOS_ON_GPU
+            on_gpu = targets[i] == dos.DOS_ON_GPU and (residents[i] or not spill_all_grads)
             g = self.g[i] if on_gpu else self.hg[i]
             arr[i] = dos.dos_subgroup(st[0].data_ptr(), st[1].data_ptr(), st[2].data_ptr(), g.data_ptr(),
                                       self.lp[i].data_ptr(), n,
                                       dos.DOS_DEVICE if residents[i] else dos.DOS_HOST_PINNED,
                                       dos.DOS_DEVICE if on_gpu else dos.DOS_HOST_PINNED)
         self.targets = list(targets)
+        self.grads_on_host = [not (targets[i] == dos.DOS_ON_GPU and (residents[i] or not spill_all_grads))
+                              for i in range(n_sg)]
         self.sgs = arr
         return arr
 
     def sync_host_grads(self):
-        """Spill the gradients of CPU-planned subgroups to their pinned copies."""
+        """Spill the gradients the descriptors expect in pinned host memory."""
         for i in range(len(self.sizes)):
-            if self.targets[i] == dos.DOS_ON_CPU:
+            if self.grads_on_host[i]:
                 self.hg[i].copy_(self.g[i], non_blocking=True)
         torch.cuda.synchronize()
 
