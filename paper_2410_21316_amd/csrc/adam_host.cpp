@@ -57,8 +57,12 @@ inline uint16_t bf16_rne_host(float x) {
 }
 
 // The loop the compiler vectorises.  Clones for wider vector units are picked at
-// load time; all of them perform the same IEEE operations.
+// load time; all of them perform the same IEEE operations.  (Sanitizer builds
+// define DOS_NO_TARGET_CLONES: the load-time resolver runs before their runtime
+// is up.)
+#ifndef DOS_NO_TARGET_CLONES
 __attribute__((target_clones("avx512f", "avx2", "default")))
+#endif
 void adam_block(float* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
                 const uint16_t* __restrict__ g, uint16_t* __restrict__ p_lp, uint64_t n,
                 const AdamScalars s) {

@@ -1,0 +1,150 @@
+// Runs dos_run_update_phase on the CPU against the stand-in HIP runtime (see
+// hip_stub/): the "device" kernels below are the library's own host update, so
+// the result must equal dos_adam_step_host bit for bit.  Built by
+// tests/test_sanitizers.py with phase.cpp, plan.cpp and adam_host.cpp under
+// ASan/UBSan and under TSan (worker pool, upload ring, lane timers).
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <random>
+#include <vector>
+
+#include "dos_internal.h"
+
+namespace dos {
+void note_hip_error(int, const char*) {}
+dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
+                       const AdamScalars& s, void*, const dos_launch_cfg*) {
+  host_adam_range(p, m, v, g, p_lp, n, s);
+  return DOS_OK;
+}
+dos_status launch_pull_copy_u16(uint16_t* dst, const uint16_t* src, uint64_t n, void*) {
+  memcpy(dst, src, n * 2);
+  return DOS_OK;
+}
+}  // namespace dos
+
+static int fail(const char* what) {
+  fprintf(stderr, "phase_driver: %s\n", what);
+  return 1;
+}
+
+struct Arrays {
+  std::vector<float*> p, m, v;
+  std::vector<uint16_t*> g, lp;
+};
+
+static void* aligned(size_t bytes) {
+  void* q = nullptr;
+  if (posix_memalign(&q, 256, bytes ? bytes : 256)) abort();
+  return q;
+}
+
+int main() {
+  std::mt19937_64 rng(77);
+  for (int it = 0; it < 40; ++it) {
+    const int n_sg = 1 + (int)(rng() % 9);
+    std::vector<uint64_t> sizes(n_sg);
+    for (auto& s : sizes) s = (rng() % 5 == 0) ? rng() % 70 : rng() % 300000;
+    const int n_slots = (int)(rng() % 4);                       // 0 = no staging at all
+    const uint64_t slot_params = 64 * (1 + rng() % 2000);
+    const bool slots_hold_grads = rng() % 2;
+    const uint64_t chunk = 64 * (1 + rng() % 500);
+    const int ring = 2 + (int)(rng() % 6);
+    const int threads = 1 + (int)(rng() % 6);
+
+    Arrays a, b;  // a: through the phase, b: straight through dos_adam_step_host
+    std::vector<dos_subgroup> sgs(n_sg), ref(n_sg);
+    std::vector<uint8_t> target(n_sg), resident(n_sg, 0);
+    std::vector<int32_t> order(n_sg);
+    for (int i = 0; i < n_sg; ++i) order[i] = i;
+    std::shuffle(order.begin(), order.end(), rng);
+    for (int i = 0; i < n_sg; ++i) {
+      const uint64_t n = sizes[i];
+      target[i] = (n_slots > 0) ? (uint8_t)(rng() % 2) : DOS_ON_CPU;
+      const bool is_resident = target[i] == DOS_ON_GPU && rng() % 4 == 0;
+      const bool grads_on_device = target[i] == DOS_ON_GPU && (is_resident || !slots_hold_grads || rng() % 2);
+      for (Arrays* x : {&a, &b}) {
+        x->p.push_back((float*)aligned(n * 4));
+        x->m.push_back((float*)aligned(n * 4));
+        x->v.push_back((float*)aligned(n * 4));
+        x->g.push_back((uint16_t*)aligned(n * 2));
+        x->lp.push_back((uint16_t*)aligned(n * 2));
+      }
+      for (uint64_t k = 0; k < n; ++k) {
+        a.p[i][k] = b.p[i][k] = 0.01f * (float)((int)(rng() % 200) - 100);
+        a.m[i][k] = b.m[i][k] = 0.0f;
+        a.v[i][k] = b.v[i][k] = 0.0f;
+        a.g[i][k] = b.g[i][k] = (uint16_t)(((rng() % 2) ? 0x3A00 : 0xBA00) + rng() % 256);
+        a.lp[i][k] = b.lp[i][k] = 0;
+      }
+      sgs[i] = dos_subgroup{a.p[i], a.m[i], a.v[i], a.g[i], a.lp[i], n,
+                            is_resident ? DOS_DEVICE : DOS_HOST_PINNED,
+                            grads_on_device ? DOS_DEVICE : DOS_HOST_PINNED};
+      ref[i] = dos_subgroup{b.p[i], b.m[i], b.v[i], b.g[i], b.lp[i], n, DOS_HOST_PINNED, DOS_HOST_PINNED};
+    }
+    const uint64_t bpp = slots_hold_grads ? 14 : 12;
+    void* slot_mem = aligned((uint64_t)(n_slots ? n_slots : 1) * bpp * slot_params);
+    void* stage = aligned((uint64_t)ring * chunk * 2);
+    dos_ctx_config cfg{};
+    cfg.slot_mem = n_slots ? slot_mem : nullptr;
+    cfg.slot_bytes = (uint64_t)n_slots * bpp * slot_params;
+    cfg.slot_params = slot_params;
+    cfg.n_slots = n_slots;
+    cfg.host_threads = threads;
+    cfg.pinned_stage = stage;
+    cfg.pinned_stage_bytes = (uint64_t)ring * chunk * 2;
+    cfg.upload_chunk_params = chunk;
+    cfg.flags = (it % 2) ? DOS_CTX_PROFILE : 0;
+    dos_ctx* ctx = nullptr;
+    if (dos_ctx_create(&ctx, &cfg) != DOS_OK) return fail("dos_ctx_create failed");
+    dos_plan plan{};
+    plan.n_sg = n_sg;
+    plan.n_slots = n_slots;
+    plan.slot_params = slot_params;
+    plan.target = target.data();
+    plan.order = order.data();
+    plan.resident = resident.data();
+    for (int64_t step = 1; step <= 3; ++step) {
+      dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, step};
+      dos_phase_stats st{};
+      const dos_status rc = dos_run_update_phase(ctx, sgs.data(), n_sg, &plan, &hp, &st);
+      if (rc != DOS_OK) {
+        fprintf(stderr, "status %d\n", (int)rc);
+        return fail("dos_run_update_phase failed");
+      }
+      uint64_t total = 0;
+      for (auto s : sizes) total += s;
+      if (st.params_gpu + st.params_cpu + st.params_resident != total) return fail("stats do not add up");
+      for (int i = 0; i < n_sg; ++i) {
+        if (dos_adam_step_host(&ref[i], &hp, 1) != DOS_OK) return fail("dos_adam_step_host failed");
+        const uint64_t n = sizes[i];
+        if (memcmp(a.p[i], b.p[i], n * 4) || memcmp(a.m[i], b.m[i], n * 4) || memcmp(a.v[i], b.v[i], n * 4) ||
+            memcmp(a.lp[i], b.lp[i], n * 2))
+          return fail("phase result differs from the direct host update");
+      }
+    }
+    // a plan the context cannot serve must be refused before anything is touched
+    if (n_slots == 0 && n_sg > 0 && sizes[0] > 0) {
+      std::vector<uint8_t> all_gpu(n_sg, DOS_ON_GPU);
+      dos_plan bad = plan;
+      bad.target = all_gpu.data();
+      dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, 4};
+      std::vector<float> before(a.p[0], a.p[0] + sizes[0]);
+      if (dos_run_update_phase(ctx, sgs.data(), n_sg, &bad, &hp, nullptr) != DOS_EBUDGET)
+        return fail("GPU plan without slots accepted");
+      if (memcmp(before.data(), a.p[0], sizes[0] * 4)) return fail("state touched by a refused call");
+    }
+    dos_ctx_destroy(ctx);
+    for (Arrays* x : {&a, &b})
+      for (int i = 0; i < n_sg; ++i) {
+        free(x->p[i]); free(x->m[i]); free(x->v[i]); free(x->g[i]); free(x->lp[i]);
+      }
+    free(slot_mem);
+    free(stage);
+  }
+  printf("phase_driver ok\n");
+  return 0;
+}

@@ -158,6 +158,31 @@ def test_transfers_overlap_full_duplex(hp):
     assert stats.duplex_overlap_s > stats.d2h_busy_s / 4 > 0.0
 
 
+def test_phase_allocates_no_device_memory(hp):
+    """Section 4.1: interleaving must not allocate; slots, ring, streams and events
+    are the context's.  Free device memory is the same before and after phases."""
+    from paper_2410_21316_amd import workloads as W
+    sizes = [3_000_000, 2_000_001, 4_000_000, 1_000_000]
+    state = W.OffloadedState(sizes, S.BASE_SEED + 9)
+    ctx = W.make_context(3, 1 << 20, 4, chunk_params=1 << 18, ring_chunks=8)
+    plan = dos.Plan.manual([1, 0, 1, 0], None, 3, 1 << 20)
+    state.place(plan.targets)
+    state.sync_host_grads()
+    try:
+        ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=1, **hp))     # first call loads the kernels
+        torch.cuda.synchronize()
+        free_before, _ = torch.cuda.mem_get_info()
+        for step in (2, 3, 4):
+            ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp))
+        torch.cuda.synchronize()
+        free_after, _ = torch.cuda.mem_get_info()
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        state.free()
+    assert free_after == free_before
+
+
 def test_calibration_reports_plausible_rates():
     ctx = make_context(2, 4 << 20, host_threads=8, chunk_params=1 << 20, ring_chunks=16)
     cm = ctx.dos_calibrate()

@@ -234,3 +234,33 @@ def test_cost_model_observe_takes_the_measured_rates():
     assert (cm3.h2d_Bps, cm3.d2h_Bps, cm3.cpu_params_per_s) == (56e9, 48e9, 8e9)
     lib = dos.load()
     assert lib.dos_cost_model_observe(None, C.byref(st)) == dos.DOS_EINVAL
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_balanced_plan_invariants_on_random_machines(seed):
+    """Whatever the rates: the balanced plan is never worse (by its own estimate)
+    than all-CPU, all-GPU or any stride of Algorithm 1; its order is a permutation;
+    scaling every subgroup by the same factor keeps the placement (the paper's
+    observation that the split does not depend on the subgroup size, Section 4.2)."""
+    rng = random.Random(500 + seed)
+    n = rng.choice([5, 17, 40, 130, 260])
+    base = rng.choice([50, 100, 200, 400]) * 1_000_000
+    sizes = [base] * n if rng.random() < 0.5 else [int(base * rng.uniform(0.5, 1.5)) for _ in range(n)]
+    cost = dict(h2d_Bps=rng.uniform(10, 64) * 1e9, d2h_Bps=rng.uniform(10, 64) * 1e9,
+                gpu_params_per_s=rng.uniform(20, 250) * 1e9, cpu_params_per_s=rng.uniform(0.3, 20) * 1e9,
+                launch_overhead_s=0.0)
+    cm = dos.cost_model(cost["h2d_Bps"], cost["d2h_Bps"], cost["gpu_params_per_s"], cost["cpu_params_per_s"], 0.0, 0.0)
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9)
+    kw = dict(n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost)
+    assert sorted(plan.orders) == list(range(n))
+    assert set(plan.targets) <= {0, 1}
+    mine = ref.phase_cost(sizes, plan.targets, **kw)[0]
+    assert plan.c.predicted_s == pytest.approx(mine, rel=1e-12)
+    assert plan.c.lower_bound_s <= plan.c.predicted_s * (1 + 1e-12)
+    for other in ([0] * n, [1] * n, *(ref.stride_targets(n, k) for k in range(2, 7))):
+        assert mine <= ref.phase_cost(sizes, other, **kw)[0] * (1 + 1e-9)
+    if len(set(sizes)) == 1 and n > 16:
+        # equal subgroups: the same placement for 3x larger subgroups (slots already at the 16 Mi cap)
+        big = dos.dos_plan_subgroups(cm, [3 * s for s in sizes], 40 * 10**9)
+        assert big.targets == plan.targets
+        assert big.c.predicted_s == pytest.approx(3 * plan.c.predicted_s, rel=0.02)
