@@ -48,7 +48,12 @@ typedef enum dos_status {
   DOS_ESTATE = -5   /* memory location and requested target do not fit together      */
 } dos_status;
 
-typedef enum dos_loc { DOS_HOST_PINNED = 0, DOS_DEVICE = 1 } dos_loc;
+typedef enum dos_loc {
+  DOS_HOST_PINNED = 0,   /* page-locked host memory: the DMA engines can reach it           */
+  DOS_DEVICE = 1,        /* device memory                                                   */
+  DOS_HOST_PAGEABLE = 2  /* ordinary host memory: only the host cores touch it, so only a
+                            CPU-planned subgroup may live there                             */
+} dos_loc;
 typedef enum dos_target { DOS_ON_CPU = 0, DOS_ON_GPU = 1 } dos_target;
 
 /* One subgroup of the flat optimizer partition (Section 2 "ZeRO": a rank's
@@ -155,10 +160,14 @@ typedef struct dos_plan {
  * 64 Ki parameters per slot is DOS_EBUDGET.  With n_resident_max > 0
  * the planner may mark up to that many trailing subgroups as static residents
  * if they fit the budget next to the staging slots (Section 4.1: residents are
- * placed last). */
-dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, int32_t n_sg,
-                              uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot, int32_t mode,
-                              int32_t n_resident_max, dos_plan* out);
+ * placed last).
+ * cpu_only (n_sg entries, or NULL for none) marks subgroups that must stay on the
+ * host cores -- those whose state is in pageable host memory because the machine
+ * cannot pin all of it.  They are never GPU-planned or resident; the stride of
+ * mode DOS_PLAN_STRIDE then counts over the remaining subgroups only. */
+dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only,
+                              int32_t n_sg, uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
+                              int32_t mode, int32_t n_resident_max, dos_plan* out);
 
 /* The makespan estimate the balanced mode minimises, for any assignment:
  * predicted = max(host lane, GPU lane), lower = max(link time per direction).
@@ -258,9 +267,10 @@ dos_status dos_pinned_free(void* ptr);
  * give the scale of the same counters read for the AdamW kernel. */
 dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
 
-/* Reads one byte of every 4 KiB page of a host buffer with `threads` threads, so
- * that the first host update of a buffer that so far was only written by DMA does
- * not pay for the page faults inside the update phase. */
+/* Reads one byte of every 4 KiB page of a host buffer and writes it back, with
+ * `threads` threads, so that the first host update of a buffer that so far was
+ * only written by DMA, or never touched, does not pay for the page faults inside
+ * the update phase.  Nobody else may write the buffer during the call. */
 dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads);
 
 const char* dos_strerror(dos_status s);

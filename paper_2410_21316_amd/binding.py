@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdos.so")
 
 DOS_OK, DOS_EINVAL, DOS_EALIGN, DOS_EBUDGET, DOS_EHIP, DOS_ESTATE = 0, -1, -2, -3, -4, -5
-DOS_HOST_PINNED, DOS_DEVICE = 0, 1
+DOS_HOST_PINNED, DOS_DEVICE, DOS_HOST_PAGEABLE = 0, 1, 2
 DOS_ON_CPU, DOS_ON_GPU = 0, 1
 DOS_PLAN_STRIDE, DOS_PLAN_BALANCED = 0, 1
 DOS_CTX_PROFILE = 1
@@ -77,7 +77,7 @@ SIGNATURES = {
     "dos_adam_step_cfg": (C.c_int, [C.POINTER(dos_subgroup), C.POINTER(dos_hparams), C.c_void_p,
                                     C.POINTER(dos_launch_cfg)]),
     "dos_adam_step_host": (C.c_int, [C.POINTER(dos_subgroup), C.POINTER(dos_hparams), C.c_int32]),
-    "dos_plan_subgroups": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(C.c_uint64), C.c_int32,
+    "dos_plan_subgroups": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(C.c_uint64), C.POINTER(C.c_uint8), C.c_int32,
                                      C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
                                      C.POINTER(dos_plan)]),
     "dos_plan_cost": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(C.c_uint64),
@@ -223,11 +223,12 @@ def cost_model(h2d_Bps, d2h_Bps, gpu_params_per_s, cpu_params_per_s, downscale_p
 
 
 def dos_plan_subgroups(cm: dos_cost_model, sizes, gpu_budget_bytes: int, mode: int = DOS_PLAN_BALANCED,
-                       n_resident_max: int = 0, bytes_per_param_slot: int = 12) -> Plan:
+                       n_resident_max: int = 0, bytes_per_param_slot: int = 12, cpu_only=None) -> Plan:
     n = len(sizes)
     arr = (C.c_uint64 * max(n, 1))(*[int(s) for s in sizes])
+    mask = (C.c_uint8 * max(n, 1))(*[int(bool(x)) for x in cpu_only]) if cpu_only is not None else None
     pl = Plan(n)
-    check(load().dos_plan_subgroups(C.byref(cm), arr, n, int(gpu_budget_bytes),
+    check(load().dos_plan_subgroups(C.byref(cm), arr, mask, n, int(gpu_budget_bytes),
                                     int(bytes_per_param_slot), int(mode), int(n_resident_max),
                                     C.byref(pl.c)), "dos_plan_subgroups")
     return pl

@@ -97,7 +97,10 @@ extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hpara
   rc = dos::make_scalars(hp, &s);
   if (rc != DOS_OK) return rc;
   if (sg->n == 0) return DOS_OK;
-  if (sg->state_loc != DOS_HOST_PINNED || sg->grad_loc != DOS_HOST_PINNED) return DOS_ESTATE;
+  if (sg->state_loc == DOS_DEVICE || sg->grad_loc == DOS_DEVICE) return DOS_ESTATE;
+  if (sg->state_loc < DOS_HOST_PINNED || sg->state_loc > DOS_HOST_PAGEABLE || sg->grad_loc < DOS_HOST_PINNED ||
+      sg->grad_loc > DOS_HOST_PAGEABLE)
+    return DOS_EINVAL;
   const uint64_t n = sg->n;
   int T = threads < 1 ? 1 : threads;
   const uint64_t min_per_thread = 1u << 16;

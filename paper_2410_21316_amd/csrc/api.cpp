@@ -79,12 +79,16 @@ dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {
   if ((uint64_t)T > pages) T = (int)pages;
   std::vector<std::thread> pool;
   std::atomic<uint64_t> sink{0};
-  const volatile unsigned char* base = static_cast<const volatile unsigned char*>(ptr);
+  volatile unsigned char* base = static_cast<volatile unsigned char*>(ptr);
   for (int t = 0; t < T; ++t) {
     const uint64_t lo = pages * t / T, hi = pages * (t + 1) / T;
     pool.emplace_back([=, &sink] {
       uint64_t acc = 0;
-      for (uint64_t pg = lo; pg < hi; ++pg) acc += base[pg * page];
+      for (uint64_t pg = lo; pg < hi; ++pg) {
+        const unsigned char b = base[pg * page];
+        base[pg * page] = b;  // a write fault gives the page real memory, not the shared zero page
+        acc += b;
+      }
       sink.fetch_add(acc, std::memory_order_relaxed);
     });
   }

@@ -364,11 +364,12 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
     const dos_subgroup& sg = sgs[i];
     if ((rc = dos::check_subgroup_pointers(&sg)) != DOS_OK) return rc;
     if (plan->target[i] > DOS_ON_GPU) return DOS_EINVAL;
-    if (sg.state_loc != DOS_HOST_PINNED && sg.state_loc != DOS_DEVICE) return DOS_EINVAL;
-    if (sg.grad_loc != DOS_HOST_PINNED && sg.grad_loc != DOS_DEVICE) return DOS_EINVAL;
+    if (sg.state_loc < DOS_HOST_PINNED || sg.state_loc > DOS_HOST_PAGEABLE) return DOS_EINVAL;
+    if (sg.grad_loc < DOS_HOST_PINNED || sg.grad_loc > DOS_HOST_PAGEABLE) return DOS_EINVAL;
     if (sg.n == 0) continue;
     if (plan->target[i] == DOS_ON_CPU) {
-      if (sg.state_loc != DOS_HOST_PINNED || sg.grad_loc != DOS_HOST_PINNED) return DOS_ESTATE;
+      // the host cores read and write it in place: pinned or pageable, but not device memory
+      if (sg.state_loc == DOS_DEVICE || sg.grad_loc == DOS_DEVICE) return DOS_ESTATE;
       if (c->ring_n < 2) return DOS_EBUDGET;
       for (uint64_t off = 0; off < sg.n; off += c->chunk_params)
         chunks.push_back({i, off, std::min(c->chunk_params, sg.n - off)});
@@ -379,6 +380,8 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       params_res += sg.n;
       ++n_res;
     } else {
+      // the DMA engines must reach it: pageable state or gradients cannot be staged
+      if (sg.state_loc == DOS_HOST_PAGEABLE || sg.grad_loc == DOS_HOST_PAGEABLE) return DOS_ESTATE;
       if (c->n_slots < 1) return DOS_EBUDGET;
       if (sg.grad_loc == DOS_HOST_PINNED && !c->slots_hold_grads) return DOS_EBUDGET;
       for (uint64_t off = 0; off < sg.n; off += c->slot_params)

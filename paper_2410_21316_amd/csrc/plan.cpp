@@ -86,8 +86,8 @@ extern "C" dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* si
   return DOS_OK;
 }
 
-extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, int32_t n_sg,
-                                         uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
+extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only,
+                                         int32_t n_sg, uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
                                          int32_t mode, int32_t n_resident_max, dos_plan* out) {
   if (!valid_cost_model(cm) || !out || n_sg < 0 || n_resident_max < 0) return DOS_EINVAL;
   if (mode != DOS_PLAN_STRIDE && mode != DOS_PLAN_BALANCED) return DOS_EINVAL;
@@ -117,7 +117,11 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   // ---- static residents: trailing subgroups that fit next to the slots
   uint64_t left = gpu_budget_bytes - std::min<uint64_t>(gpu_budget_bytes, (uint64_t)n_slots * bpp * slot_params);
   int n_res = 0;
-  for (int i = n_sg - 1; i >= 0 && n_res < n_resident_max; --i) {
+  std::vector<int> movable;  // subgroups that may leave the host cores, in index order
+  for (int i = 0; i < n_sg; ++i)
+    if (!cpu_only || !cpu_only[i]) movable.push_back(i);
+  for (int q = (int)movable.size() - 1; q >= 0 && n_res < n_resident_max; --q) {
+    const int i = movable[q];
     const uint64_t need = 12 * sizes[i];
     if (need > left) break;
     left -= need;
@@ -125,7 +129,8 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
     target[i] = DOS_ON_GPU;
     ++n_res;
   }
-  const int n_dyn = n_sg - n_res;
+  movable.resize(movable.size() - (size_t)n_res);  // what is left can be planned dynamically
+  const int n_dyn = (int)movable.size();
 
   // ---- Eq. 1 (reported in both modes)
   const double B = cm->h2d_Bps / 4.0;  // link rate in FP32 parameters per second
@@ -143,14 +148,14 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   };
 
   if (mode == DOS_PLAN_STRIDE) {
-    for (int i = 0; i < n_dyn; ++i)
-      if (k >= 1 && (i + 1) % k == 0) target[i] = DOS_ON_GPU;
+    for (int q = 0; q < n_dyn; ++q)
+      if (k >= 1 && (q + 1) % k == 0) target[movable[q]] = DOS_ON_GPU;
   } else if (n_dyn <= 16) {
     // few subgroups: every assignment is tried
     std::vector<uint8_t> best = target, cand = target;
     double best_cost = cost_of(best).predicted;
     for (uint32_t bits = 1; bits < (1u << n_dyn); ++bits) {
-      for (int i = 0; i < n_dyn; ++i) cand[i] = (bits >> i) & 1u;
+      for (int q = 0; q < n_dyn; ++q) cand[movable[q]] = (bits >> q) & 1u;
       const double cc = cost_of(cand).predicted;
       if (cc < best_cost) {
         best_cost = cc;
@@ -164,8 +169,8 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
     std::vector<uint8_t> best = target, cand = target;
     double best_cost = cost_of(best).predicted;
     for (int c = 1; c <= n_dyn; ++c) {
-      for (int i = 0; i < n_dyn; ++i)
-        cand[i] = ((int64_t)(i + 1) * c / n_dyn > (int64_t)i * c / n_dyn) ? DOS_ON_GPU : DOS_ON_CPU;
+      for (int q = 0; q < n_dyn; ++q)
+        cand[movable[q]] = ((int64_t)(q + 1) * c / n_dyn > (int64_t)q * c / n_dyn) ? DOS_ON_GPU : DOS_ON_CPU;
       const double cc = cost_of(cand).predicted;
       if (cc < best_cost) {
         best_cost = cc;
@@ -177,7 +182,8 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
     bool improved = true;
     for (int pass = 0; improved && pass < 64; ++pass) {
       improved = false;
-      for (int i = 0; i < n_dyn; ++i) {
+      for (int q = 0; q < n_dyn; ++q) {
+        const int i = movable[q];
         best[i] ^= 1;
         const double cc = cost_of(best).predicted;
         if (cc < best_cost * (1.0 - 1e-12)) {
@@ -188,8 +194,9 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
         }
       }
       if (n_dyn <= 96) {
-        for (int i = 0; i < n_dyn; ++i)
-          for (int j = i + 1; j < n_dyn; ++j) {
+        for (int qi = 0; qi < n_dyn; ++qi)
+          for (int qj = qi + 1; qj < n_dyn; ++qj) {
+            const int i = movable[qi], j = movable[qj];
             if (best[i] == best[j] || sizes[i] == sizes[j]) continue;
             std::swap(best[i], best[j]);
             const double cc = cost_of(best).predicted;

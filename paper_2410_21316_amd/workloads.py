@@ -76,27 +76,36 @@ class OffloadedState:
     (GPU-planned) or at the pinned copy (CPU-planned) and moves static residents'
     state to the device, following the plan as Section 4.1 describes."""
 
-    def __init__(self, sizes, seed=S.BASE_SEED, device="cuda:0", fill=True, pinned_reserve_bytes=0):
-        """If the machine cannot pin all of it, the state is cut after the last
-        subgroup that fits (leaving `pinned_reserve_bytes` for the caller's own
-        pinned buffers); `self.sizes` then tells what was built."""
+    def __init__(self, sizes, seed=S.BASE_SEED, device="cuda:0", fill=True, pinned_reserve_bytes=0,
+                 pageable_rest=False, pin_at_most=None):
+        """If the machine cannot pin all of it (leaving `pinned_reserve_bytes` for
+        the caller's own pinned buffers), the subgroups that do not fit either
+        live in ordinary pageable host memory (`pageable_rest=True`: they can then
+        only be updated by the host cores, `self.cpu_only` marks them) or are
+        dropped (`self.truncated`, `self.sizes` tells what was built).
+        `pin_at_most` caps the number of pinned subgroups (for tests)."""
         self.sizes, self.seed, self.device = list(sizes), seed, device
         self.blocks, self.hp, self.hm, self.hv, self.hg = [], [], [], [], []
         self.truncated = False
         try:
             reserve = PinnedBlock(pinned_reserve_bytes) if pinned_reserve_bytes else None
-            for n in self.sizes:
+            for n in self.sizes[:pin_at_most]:
                 fb, gb = _round_up(4 * n, 4096), _round_up(2 * n, 4096)
                 self.blocks.append(PinnedBlock(3 * fb + gb))
         except dos.DosError as e:
             if e.status != dos.DOS_EHIP or not self.blocks:
                 raise
-            self.truncated = True
-            self.sizes = self.sizes[:len(self.blocks)]
+            if not pageable_rest:
+                self.truncated = True
+                self.sizes = self.sizes[:len(self.blocks)]
         finally:
             if pinned_reserve_bytes and reserve is not None:
                 reserve.free()
+        if pin_at_most is not None and not pageable_rest:
+            self.sizes = self.sizes[:len(self.blocks)]
         n_sg = len(self.sizes)
+        self.n_pinned = len(self.blocks)
+        self.cpu_only = [i >= self.n_pinned for i in range(n_sg)]
         self.lp = [torch.zeros(n, dtype=torch.bfloat16, device=device) for n in self.sizes]
         self.g = [torch.zeros(n, dtype=torch.bfloat16, device=device) for n in self.sizes]
         self.res = [None] * n_sg                      # device p, m, v of static residents
@@ -104,18 +113,27 @@ class OffloadedState:
         tmp = torch.empty(max(self.sizes), dtype=torch.float32, device=device)
         for i, n in enumerate(self.sizes):
             fb = _round_up(4 * n, 4096)
-            blk = self.blocks[i]
-            self.hp.append(blk.tensor(torch.float32, 0, n))
-            self.hm.append(blk.tensor(torch.float32, fb, n))
-            self.hv.append(blk.tensor(torch.float32, 2 * fb, n))
-            self.hg.append(blk.tensor(torch.bfloat16, 3 * fb, n))
+            if i < self.n_pinned:
+                blk = self.blocks[i]
+                self.hp.append(blk.tensor(torch.float32, 0, n))
+                self.hm.append(blk.tensor(torch.float32, fb, n))
+                self.hv.append(blk.tensor(torch.float32, 2 * fb, n))
+                self.hg.append(blk.tensor(torch.bfloat16, 3 * fb, n))
+            else:                                     # ordinary host memory, 64-byte aligned by torch
+                self.hp.append(torch.empty(n, dtype=torch.float32))
+                self.hm.append(torch.zeros(n, dtype=torch.float32))
+                self.hv.append(torch.zeros(n, dtype=torch.float32))
+                self.hg.append(torch.empty(n, dtype=torch.bfloat16))
+                for t in (self.hp[i], self.hm[i], self.hv[i], self.hg[i]):
+                    dos.dos_host_prefault(t.data_ptr(), t.numel() * t.element_size(), 16)
             if fill:
                 S.fill_chunked(lambda start, count: S.params(seed, i, start, count, device), tmp[:n])
                 self.hp[i].copy_(tmp[:n])
-                self.hm[i].copy_(zeros[:n])
-                self.hv[i].copy_(zeros[:n])
-                # the fill came in by DMA: map the pages for the host cores too
-                dos.dos_host_prefault(blk.ptr, blk.nbytes, 16)
+                if i < self.n_pinned:
+                    self.hm[i].copy_(zeros[:n])
+                    self.hv[i].copy_(zeros[:n])
+                    # the fill came in by DMA: map the pages for the host cores too
+                    dos.dos_host_prefault(self.blocks[i].ptr, self.blocks[i].nbytes, 16)
         del zeros, tmp
         self.targets = [dos.DOS_ON_CPU] * n_sg
         self.grads_on_host = [True] * n_sg
@@ -147,10 +165,12 @@ class OffloadedState:
             st = self.res[i] if residents[i] else (self.hp[i], self.hm[i], self.hv[i])
             on_gpu = targets[i] == dos.DOS_ON_GPU and (residents[i] or not spill_all_grads)
             g = self.g[i] if on_gpu else self.hg[i]
+            host = dos.DOS_HOST_PAGEABLE if self.cpu_only[i] else dos.DOS_HOST_PINNED
+            assert not (self.cpu_only[i] and (targets[i] == dos.DOS_ON_GPU or residents[i]))
             arr[i] = dos.dos_subgroup(st[0].data_ptr(), st[1].data_ptr(), st[2].data_ptr(), g.data_ptr(),
                                       self.lp[i].data_ptr(), n,
-                                      dos.DOS_DEVICE if residents[i] else dos.DOS_HOST_PINNED,
-                                      dos.DOS_DEVICE if on_gpu else dos.DOS_HOST_PINNED)
+                                      dos.DOS_DEVICE if residents[i] else host,
+                                      dos.DOS_DEVICE if on_gpu else host)
         self.targets = list(targets)
         self.grads_on_host = [not (targets[i] == dos.DOS_ON_GPU and (residents[i] or not spill_all_grads))
                               for i in range(n_sg)]

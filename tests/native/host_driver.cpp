@@ -35,7 +35,9 @@ int main() {
     plan.order = order.data();
     plan.resident = resident.data();
     const uint64_t budget = (uint64_t)(1 + rng() % 64) * 1000000000ull;
-    const dos_status rc = dos_plan_subgroups(&cm, sizes.data(), n, budget, (rng() % 2) ? 12 : 14, (int)(rng() % 2),
+    std::vector<uint8_t> cpu_only(n + 1);
+    for (auto& f : cpu_only) f = (uint8_t)(rng() % 3 == 0);
+    const dos_status rc = dos_plan_subgroups(&cm, sizes.data(), (rng() % 2) ? cpu_only.data() : nullptr, n, budget, (rng() % 2) ? 12 : 14, (int)(rng() % 2),
                                              (int)(rng() % (n + 1)), &plan);
     if (rc != DOS_OK) return fail("dos_plan_subgroups failed");
     double pred = 0, low = 0;

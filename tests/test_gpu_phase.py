@@ -158,6 +158,48 @@ def test_transfers_overlap_full_duplex(hp):
     assert stats.duplex_overlap_s > stats.d2h_busy_s / 4 > 0.0
 
 
+def test_pageable_subgroups_are_updated_by_the_host_cores_only(hp):
+    """State the machine cannot pin stays in ordinary host memory: the host lane
+    updates it in place; planning it for the GPU is refused before anything runs."""
+    from paper_2410_21316_amd import workloads as W
+    from oracle import adamw_oracle as ref
+    sizes = [300_001, 200_000, 250_003, 100_000, 65]
+    state = W.OffloadedState(sizes, S.BASE_SEED + 10, pageable_rest=True, pin_at_most=2)
+    assert state.cpu_only == [False, False, True, True, True]
+    cm = dos.cost_model(50e9, 50e9, 150e9, 0.2e9)            # slow host: the planner wants the GPU
+    plan = dos.dos_plan_subgroups(cm, sizes, 64 << 20, cpu_only=state.cpu_only)
+    assert plan.targets[:2] == [1, 1] and plan.targets[2:] == [0, 0, 0]
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, 4, chunk_params=1 << 16, ring_chunks=6)
+    want = [[state.hp[i].numpy().copy(), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)]
+            for i, n in enumerate(sizes)]
+    try:
+        for step in (1, 2, 3):
+            state.place(plan.targets, plan.residents)
+            assert [sg.state_loc for sg in state.sgs] == [0, 0, 2, 2, 2]
+            state.fill_grads(step, zero_pct=1.0)
+            state.sync_host_grads()
+            ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp))
+            for i in range(len(sizes)):
+                g = state.g[i].view(torch.int16).cpu().numpy().view(np.uint16)
+                ref.adamw_step(want[i][0], want[i][1], want[i][2], g, want[i][3], step=step, **hp)
+        for i in range(len(sizes)):
+            for t, w in zip((state.hp[i], state.hm[i], state.hv[i]), want[i][:3]):
+                assert t.numpy().tobytes() == w.tobytes()
+            assert state.lp[i].view(torch.int16).cpu().numpy().view(np.uint16).tobytes() == want[i][3].tobytes()
+        # a GPU plan for a pageable subgroup is refused and nothing is touched
+        before = state.hp[2].numpy().copy()
+        bad = dos.Plan.manual([1, 1, 1, 0, 0], None, plan.c.n_slots, plan.c.slot_params)
+        lib = dos.load()
+        good_hp = dos.hparams(step=4, **hp)
+        rc = lib.dos_run_update_phase(ctx._h, state.sgs, len(sizes), C.byref(bad.c), C.byref(good_hp), None)
+        assert rc == dos.DOS_ESTATE
+        assert state.hp[2].numpy().tobytes() == before.tobytes()
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        state.free()
+
+
 def test_phase_allocates_no_device_memory(hp):
     """Section 4.1: interleaving must not allocate; slots, ring, streams and events
     are the context's.  Free device memory is the same before and after phases."""

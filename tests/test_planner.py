@@ -181,7 +181,7 @@ def test_planner_rejects_bad_arguments():
     pl = dos.Plan(4)
 
     def call(cm_=cm, n=4, budget=10**9, bpp=12, mode=1, nres=0, out=pl.c, sz=sizes):
-        return lib.dos_plan_subgroups(C.byref(cm_) if cm_ is not None else None, sz, n, budget, bpp, mode, nres,
+        return lib.dos_plan_subgroups(C.byref(cm_) if cm_ is not None else None, sz, None, n, budget, bpp, mode, nres,
                                       C.byref(out) if out is not None else None)
 
     assert call() == dos.DOS_OK
@@ -264,3 +264,40 @@ def test_balanced_plan_invariants_on_random_machines(seed):
         big = dos.dos_plan_subgroups(cm, [3 * s for s in sizes], 40 * 10**9)
         assert big.targets == plan.targets
         assert big.c.predicted_s == pytest.approx(3 * plan.c.predicted_s, rel=0.02)
+
+
+def test_cpu_only_subgroups_are_never_moved_to_the_gpu():
+    """Subgroups whose state sits in pageable host memory must stay on the host
+    cores; the rest is planned as usual, and for few subgroups still optimally."""
+    rng = random.Random(11)
+    cm = dos.cost_model(COST["h2d_Bps"], COST["d2h_Bps"], COST["gpu_params_per_s"], 3e9, 0.0, COST["launch_overhead_s"])
+    cost = {**COST, "cpu_params_per_s": 3e9}
+    for n in (6, 12, 40, 130):
+        sizes = [rng.randint(40, 160) * 1_000_000 for _ in range(n)]
+        mask = [rng.random() < 0.5 for _ in range(n)]
+        for mode in (dos.DOS_PLAN_BALANCED, dos.DOS_PLAN_STRIDE):
+            plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, mode, n_resident_max=3, cpu_only=mask)
+            for t, r, forced in zip(plan.targets, plan.residents, mask):
+                assert not (forced and (t or r))
+            # residents are the last movable subgroups
+            movable = [i for i in range(n) if not mask[i]]
+            assert [i for i in range(n) if plan.residents[i]] == movable[len(movable) - sum(plan.residents):]
+        if n <= 12:
+            plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, cpu_only=mask)
+            free = [i for i in range(n) if not mask[i]]
+            best = None
+            for bits in range(1 << len(free)):
+                t = [0] * n
+                for q, i in enumerate(free):
+                    t[i] = (bits >> q) & 1
+                c = ref.phase_cost(sizes, t, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost)[0]
+                best = c if best is None else min(best, c)
+            assert plan.c.predicted_s <= best * (1 + 1e-12)
+    # stride mode counts over the movable subgroups only
+    mask = [0, 1, 0, 0, 1, 0, 0, 0]
+    cmp_ = cm_from_paper_units(3 * G, 35 * G, 2 * G, 8.7 * G)          # k = 2
+    plan = dos.dos_plan_subgroups(cmp_, [10_000_000] * 8, 10**9, dos.DOS_PLAN_STRIDE, cpu_only=mask)
+    assert plan.targets == [0, 0, 1, 0, 0, 1, 0, 1]
+    # everything forced to the host
+    plan = dos.dos_plan_subgroups(cm, [10_000_000] * 5, 10**9, cpu_only=[1] * 5, n_resident_max=5)
+    assert plan.targets == [0] * 5 and plan.residents == [0] * 5
