@@ -378,7 +378,8 @@ def bench_ablation(args, dos, torch, np):
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     sizes = [100_000_000] * 130
-    state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30)
+    state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30,
+                             pageable_rest=args.full_size)
     sizes = list(state.sizes)
     scale = sum(sizes) / 13e9
     budget = int(40 * 10**9 * scale)
@@ -420,8 +421,8 @@ def bench_ablation(args, dos, torch, np):
                             / pair["balanced"]["update_phase_s_per_iter"]})
     state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
     state.free()
-    return {"workload": f"{len(sizes)} x 100M-parameter subgroups in pinned host memory, GPU budget "
-                        f"{budget/1e9:.1f} GB (40 GB scaled by {scale:.3f}), grads ~N(0,1e-3), 4 timed steps",
+    return {"workload": f"{len(sizes)} x 100M-parameter subgroups in host memory ({state.n_pinned} pinned), GPU "
+                        f"budget {budget/1e9:.1f} GB (40 GB scaled by {scale:.3f}), grads ~N(0,1e-3), 4 timed steps",
             "rows": rows, "host_threads_sweep": thread_rows}
 
 
@@ -434,18 +435,23 @@ def bench_c5(args, dos, torch, np):
     total_nominal = 13_000_000_000
     cells = []
     scale = None
-    for sg_params in (50_000_000, 100_000_000, 200_000_000, 400_000_000):
+    for sg_params in [int(x) * 1_000_000 for x in args.sweep_sizes.split(",")]:
         n_sg = -(-total_nominal // sg_params)
         sizes = [sg_params] * (n_sg - 1) + [total_nominal - sg_params * (n_sg - 1)]
-        if scale is not None:                      # same parameter count for every subgroup size
+        if scale is not None and scale < 1:        # same parameter count for every subgroup size
             keep = int(round(scale * total_nominal))
             n_keep = max(1, keep // sg_params)
             sizes = [sg_params] * n_keep
-        state = W.OffloadedState(sizes, S.BASE_SEED + 5, "cuda:0", pinned_reserve_bytes=1 << 30)
+        state = W.OffloadedState(sizes, S.BASE_SEED + 5, "cuda:0", pinned_reserve_bytes=1 << 30,
+                                 pageable_rest=args.full_size)
         sizes = list(state.sizes)
         if scale is None:
             scale = sum(sizes) / total_nominal
-            log(f"[c5] this machine pins {sum(sizes)/1e9:.1f}B of the 13B parameters; budgets are scaled by {scale:.3f}")
+            if scale < 1:
+                log(f"[c5] this machine pins {sum(sizes)/1e9:.1f}B of the 13B parameters; budgets are scaled "
+                    f"by {scale:.3f}")
+            else:
+                log(f"[c5] full size; {state.n_pinned} of {len(sizes)} subgroups pinned, the rest pageable (CPU-only)")
         cm = None
         for budget_gb in (8, 16, 32, 64):
             budget = int(budget_gb * 10**9 * scale)
@@ -486,6 +492,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
     ap.add_argument("--sweep", action="store_true", help="also run the c5 subgroup-size x budget sweep")
+    ap.add_argument("--sweep-sizes", default="50,100,200,400", help="subgroup sizes of the sweep, in millions")
+    ap.add_argument("--full-size", action="store_true",
+                    help="ablation / sweep on the full 13B parameters: what cannot be pinned lives in pageable host "
+                         "memory and is planned CPU-only (default: only the part that can be pinned)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (reference for traffic counters)")
     args = ap.parse_args()

@@ -161,10 +161,11 @@ typedef struct dos_plan {
  * the planner may mark up to that many trailing subgroups as static residents
  * if they fit the budget next to the staging slots (Section 4.1: residents are
  * placed last).
- * cpu_only (n_sg entries, or NULL for none) marks subgroups that must stay on the
- * host cores -- those whose state is in pageable host memory because the machine
- * cannot pin all of it.  They are never GPU-planned or resident; the stride of
- * mode DOS_PLAN_STRIDE then counts over the remaining subgroups only. */
+ * cpu_only (n_sg entries, or NULL for none) marks subgroups that cannot be staged
+ * through the GPU -- those whose state is in pageable host memory because the
+ * machine cannot pin all of it.  They are never dynamically GPU-planned (they may
+ * still be chosen as static residents: a resident's state lives on the device);
+ * the stride of mode DOS_PLAN_STRIDE counts over the stageable subgroups only. */
 dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only,
                               int32_t n_sg, uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
                               int32_t mode, int32_t n_resident_max, dos_plan* out);

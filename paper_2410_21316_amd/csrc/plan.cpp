@@ -117,11 +117,9 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   // ---- static residents: trailing subgroups that fit next to the slots
   uint64_t left = gpu_budget_bytes - std::min<uint64_t>(gpu_budget_bytes, (uint64_t)n_slots * bpp * slot_params);
   int n_res = 0;
-  std::vector<int> movable;  // subgroups that may leave the host cores, in index order
-  for (int i = 0; i < n_sg; ++i)
-    if (!cpu_only || !cpu_only[i]) movable.push_back(i);
-  for (int q = (int)movable.size() - 1; q >= 0 && n_res < n_resident_max; --q) {
-    const int i = movable[q];
+  // (a resident's state lives on the device, so it does not matter whether its
+  // host copy could be pinned: cpu_only does not exclude residency)
+  for (int i = n_sg - 1; i >= 0 && n_res < n_resident_max; --i) {
     const uint64_t need = 12 * sizes[i];
     if (need > left) break;
     left -= need;
@@ -129,7 +127,9 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
     target[i] = DOS_ON_GPU;
     ++n_res;
   }
-  movable.resize(movable.size() - (size_t)n_res);  // what is left can be planned dynamically
+  std::vector<int> movable;  // subgroups that may be staged through the GPU, in index order
+  for (int i = 0; i < n_sg; ++i)
+    if (!resident[i] && (!cpu_only || !cpu_only[i])) movable.push_back(i);
   const int n_dyn = (int)movable.size();
 
   // ---- Eq. 1 (reported in both modes)

@@ -166,7 +166,7 @@ class OffloadedState:
             on_gpu = targets[i] == dos.DOS_ON_GPU and (residents[i] or not spill_all_grads)
             g = self.g[i] if on_gpu else self.hg[i]
             host = dos.DOS_HOST_PAGEABLE if self.cpu_only[i] else dos.DOS_HOST_PINNED
-            assert not (self.cpu_only[i] and (targets[i] == dos.DOS_ON_GPU or residents[i]))
+            assert not (self.cpu_only[i] and targets[i] == dos.DOS_ON_GPU and not residents[i])
             arr[i] = dos.dos_subgroup(st[0].data_ptr(), st[1].data_ptr(), st[2].data_ptr(), g.data_ptr(),
                                       self.lp[i].data_ptr(), n,
                                       dos.DOS_DEVICE if residents[i] else host,

@@ -278,12 +278,13 @@ def test_cpu_only_subgroups_are_never_moved_to_the_gpu():
         for mode in (dos.DOS_PLAN_BALANCED, dos.DOS_PLAN_STRIDE):
             plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, mode, n_resident_max=3, cpu_only=mask)
             for t, r, forced in zip(plan.targets, plan.residents, mask):
-                assert not (forced and (t or r))
-            # residents are the last movable subgroups
-            movable = [i for i in range(n) if not mask[i]]
-            assert [i for i in range(n) if plan.residents[i]] == movable[len(movable) - sum(plan.residents):]
+                assert not (forced and t and not r)          # never staged; residency is allowed
+            # residents are the trailing subgroups (Section 4.1), whatever the mask says
+            assert plan.residents == [0] * (n - sum(plan.residents)) + [1] * sum(plan.residents)
+            assert sum(plan.residents) == 3
         if n <= 12:
             plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, cpu_only=mask)
+            assert sum(plan.residents) == 0
             free = [i for i in range(n) if not mask[i]]
             best = None
             for bits in range(1 << len(free)):
@@ -299,5 +300,5 @@ def test_cpu_only_subgroups_are_never_moved_to_the_gpu():
     plan = dos.dos_plan_subgroups(cmp_, [10_000_000] * 8, 10**9, dos.DOS_PLAN_STRIDE, cpu_only=mask)
     assert plan.targets == [0, 0, 1, 0, 0, 1, 0, 1]
     # everything forced to the host
-    plan = dos.dos_plan_subgroups(cm, [10_000_000] * 5, 10**9, cpu_only=[1] * 5, n_resident_max=5)
+    plan = dos.dos_plan_subgroups(cm, [10_000_000] * 5, 10**9, cpu_only=[1] * 5)
     assert plan.targets == [0] * 5 and plan.residents == [0] * 5
