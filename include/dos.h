@@ -226,7 +226,16 @@ typedef struct dos_phase_stats {
   int32_t n_pieces, host_threads;
 } dos_phase_stats;
 
+/* Creates a context: events, worker threads and (unless given) streams.  slot_mem
+ * and pinned_stage stay owned by the caller and must outlive the context.  A
+ * context runs one phase at a time; contexts that use the library's own streams
+ * on the same device share them, so their phases should not overlap either.
+ * Errors: DOS_EINVAL (NULL, host_threads < 1, slot_params not a multiple of 64,
+ * chunk not a multiple of 64), DOS_EALIGN (slot_mem / pinned_stage not 256-byte
+ * aligned), DOS_EBUDGET (slot_bytes < n_slots * 12 * slot_params, ring smaller
+ * than two chunks), DOS_EHIP. */
 dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg);
+/* Joins the worker threads and releases the events; NULL is allowed. */
 void dos_ctx_destroy(dos_ctx* ctx);
 
 /* One update phase over all subgroups (Algorithm 1 run_update, re-designed as
@@ -234,11 +243,14 @@ void dos_ctx_destroy(dos_ctx* ctx);
  * prefetched into a staging slot (H2D stream), updated there (compute stream)
  * and flushed back (D2H stream), slot by slot, piece by piece; static residents
  * (state_loc == DOS_DEVICE) are updated in place, last; CPU-planned subgroups
- * are updated by the host worker threads, which write the 16-bit parameters
- * into the pinned upload ring and send them to p_lp on the upload stream.
+ * (state and gradients in pinned or pageable host memory) are updated in place
+ * by the host worker threads, which write the 16-bit parameters into the pinned
+ * upload ring and send them to p_lp on the upload stream.
  * Synchronous at the boundary: on return every p, m, v is back where state_loc
- * says and every p_lp has landed on the device.  plan->target / plan->order
- * decide the placement and the order inside each lane.  Errors leave all state
+ * says and every p_lp has landed on the device.  plan->target decides the lane
+ * of each subgroup, plan->order the order in which each lane takes its subgroups
+ * (plan->n_slots, slot_params and resident are informative: the context's slots
+ * and each subgroup's state_loc are what the phase uses).  Errors leave all state
  * untouched when they are detected by validation (DOS_EINVAL, DOS_EALIGN,
  * DOS_ESTATE, DOS_EBUDGET); DOS_EHIP is sticky and state is then undefined. */
 dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
