@@ -9,7 +9,7 @@ workloads ride in the same line under "extra": the 7B-parameter resident state
 (70 x 100M) and the 13B-parameter host-offloaded state (130 x 100M, 40 GB GPU
 budget) run through dos_plan_subgroups + dos_run_update_phase.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c3,c4|none] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4|none] [--ablation] [--sweep] [--full-size]
 """
 from __future__ import annotations
 
@@ -172,6 +172,45 @@ def bench_c2(args, dos, torch, np):
     del state
     torch.cuda.empty_cache()
     return res
+
+
+def bench_c1(args, dos, torch, np):
+    """Single device-resident subgroup of 1,048,576 parameters, fresh gradients per step, 10 steps: a parity
+    configuration (29 MB per step fits the on-die caches and one launch is a few microseconds: launch-bound)."""
+    from paper_2410_21316_amd import workloads as W
+    import dos_synth as S
+    from oracle import adamw_oracle as ref
+    hp_kw = dict(S.HPARAMS)
+    n = 1 << 20
+    state = W.ResidentState([n], S.BASE_SEED + 1, "cuda:0", n_grad_sets=10)
+    for k in range(10):
+        state.fill_grads(k, k + 1)
+    want = [state.p[0].cpu().numpy(), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)]
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for step in range(1, 11):
+        dos.dos_adam_step(state.descs[step - 1][0], dos.hparams(step=step, **hp_kw), stream.cuda_stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for step in range(1, 11):
+        g = state.g[0][step - 1].view(torch.int16).cpu().numpy().view(np.uint16)
+        ref.adamw_step(want[0], want[1], want[2], g, want[3], step=step, **hp_kw)
+    mism = sum(int(np.count_nonzero(t.cpu().numpy().view(np.uint32) != w.view(np.uint32)))
+               for t, w in ((state.p[0], want[0]), (state.m[0], want[1]), (state.v[0], want[2])))
+    mism += int(np.count_nonzero(state.lp[0].view(torch.int16).cpu().numpy().view(np.uint16) != want[3]))
+    ev = e0.elapsed_time(e1) * 1e-3
+    out = {"workload": "c1: one device-resident subgroup of 1,048,576 params, fresh grads ~N(0,1e-3) per step, 10 steps",
+           "us_per_step_wall": wall / 10 * 1e6, "us_per_step_on_stream": ev / 10 * 1e6,
+           "params_per_s": n * 10 / ev, "effective_GBps": BYTES_PER_PARAM * n * 10 / ev / 1e9,
+           "note": "launch- and cache-dominated; not a roofline configuration",
+           "mismatches_vs_oracle": mism}
+    log(f"[c1] {out['us_per_step_on_stream']:.1f} us/step on the stream, mismatches {mism}")
+    return out
 
 
 def bench_c3(args, dos, torch, np):
@@ -487,7 +526,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--extra", default="c3,c4", help="comma list of extra workloads (c3, c4) or 'none'")
+    ap.add_argument("--extra", default="c1,c3,c4", help="comma list of extra workloads (c1, c3, c4) or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
@@ -515,6 +554,8 @@ def main():
     res = bench_c2(args, dos, torch, np)
     extra = {}
     wanted = [] if args.extra == "none" else [w.strip() for w in args.extra.split(",") if w.strip()]
+    if "c1" in wanted:
+        extra["c1_single_subgroup_1m"] = bench_c1(args, dos, torch, np)
     if "c3" in wanted:
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
     if "c4" in wanted:
