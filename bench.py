@@ -174,6 +174,50 @@ def bench_c2(args, dos, torch, np):
     return res
 
 
+def bench_ceilings(args, dos, torch, np):
+    """What bounds the AdamW kernel: its own launch with only the loads, only the stores, both without the
+    arithmetic, and the full kernel, on 4 x 100M-parameter subgroups (rotated, so nothing is reused from a cache)."""
+    from paper_2410_21316_amd import workloads as W
+    import dos_synth as S
+    n = 100_000_000
+    state = W.ResidentState([n] * 4, S.BASE_SEED + 7, "cuda:0")
+    state.fill_grads(0, 1)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    sh = stream.cuda_stream
+    hp = dos.hparams(step=1, **S.HPARAMS)
+
+    def rate(fn, bytes_per_param):
+        for sg in state.descs[0]:
+            fn(sg)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(4):
+            for sg in state.descs[0]:
+                fn(sg)
+        e1.record(stream)
+        stream.synchronize()
+        return bytes_per_param * n * 16 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    out = {"params_per_launch": n,
+           "note": "same launch shape as dos_adam_step: 16 B per lane, non-temporal, 64-thread blocks; "
+                   "'capped' = its cap on resident waves per compute unit, 'uncapped' = none"}
+    out["adamw_capped_GBps"] = rate(lambda sg: dos.dos_adam_step(sg, hp, sh), 28)
+    out["adamw_uncapped_GBps"] = rate(lambda sg: dos.dos_adam_step_cfg(sg, hp, sh, variant=0x74, lds_bytes=-1), 28)
+    for name, lds in (("capped", 0), ("uncapped", -1)):
+        rd = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 0, sh, lds), 14)
+        both = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 2, sh, lds), 28)
+        out[f"loads_only_{name}_GBps"] = rd
+        out[f"loads_and_stores_no_math_{name}_GBps"] = both
+    for name, lds in (("capped", 0), ("uncapped", -1)):              # last: these zero the state
+        out[f"stores_only_{name}_GBps"] = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 1, sh, lds), 14)
+    rd = max(out["loads_only_capped_GBps"], out["loads_only_uncapped_GBps"])
+    wr = max(out["stores_only_capped_GBps"], out["stores_only_uncapped_GBps"])
+    out["time_shared_mix_GBps"] = 1.0 / (0.5 / rd + 0.5 / wr)
+    log("[ceilings] " + ", ".join(f"{k} {v:.0f}" for k, v in out.items() if k.endswith("GBps")))
+    return out
+
+
 def bench_c1(args, dos, torch, np):
     """Single device-resident subgroup of 1,048,576 parameters, fresh gradients per step, 10 steps: a parity
     configuration (29 MB per step fits the on-die caches and one launch is a few microseconds: launch-bound)."""
@@ -530,6 +574,8 @@ def main():
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also measure the AdamW launch with only its loads / only its stores (HBM ceilings)")
     ap.add_argument("--sweep", action="store_true", help="also run the c5 subgroup-size x budget sweep")
     ap.add_argument("--sweep-sizes", default="50,100,200,400", help="subgroup sizes of the sweep, in millions")
     ap.add_argument("--full-size", action="store_true",
@@ -560,6 +606,8 @@ def main():
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
     if "c4" in wanted:
         extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
+    if args.ceilings:
+        extra["hbm_stream_ceilings"] = bench_ceilings(args, dos, torch, np)
     if args.ablation:
         extra["schedule_ablation"] = bench_ablation(args, dos, torch, np)
     if args.sweep:

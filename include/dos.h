@@ -87,6 +87,9 @@ typedef struct dos_launch_cfg {
   int32_t variant;       /* kernel layout variant, see dos_adam_step_cfg          */
   int32_t block_threads; /* 0 = default (64); multiple of 64, <= 512              */
   int32_t grid_blocks;   /* 0 = one tile per block; else grid-stride over tiles   */
+  int32_t lds_bytes;     /* dynamic LDS per block, used only to cap the number of
+                            resident waves per CU (160 KiB / lds_bytes blocks);
+                            0 = default, negative = none                           */
 } dos_launch_cfg;
 
 /* ---- device-resident update (Algorithm 1, gpu_update) ---------------------
@@ -101,9 +104,13 @@ dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hi
  * layout -- 0: each lane handles 4 consecutive elements per trip (16-byte FP32
  * accesses, 8-byte bf16), two trips unrolled; 1: one trip; 2: four trips; 3: each
  * lane handles 8 consecutive elements (two 16-byte FP32 accesses, 16-byte bf16);
- * bit 4 (0x10) makes the loads non-temporal, bit 5 (0x20) the stores.
- * dos_adam_step uses variant 0x31 with 64-thread blocks.  A NULL cfg means
- * those defaults; unknown values: DOS_EINVAL. */
+ * 4: one trip and no tile loop (block b owns tile b and nothing else; grid_blocks
+ * must be 0); bit 4 (0x10) makes the loads non-temporal; bits 5-6 pick the store
+ * policy: 0x20 non-temporal, 0x40 non-temporal at system scope without the
+ * wave-level bit (sc1 nt), 0x60 non-temporal at system scope (sc0 sc1 nt).
+ * dos_adam_step uses variant 0x74 with 64-thread blocks and an LDS request of
+ * 14848 bytes per block (11 one-wave blocks per compute unit).  A NULL cfg means
+ * those defaults; unknown values, lds_bytes above 65536: DOS_EINVAL. */
 dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
                              const dos_launch_cfg* cfg);
 
@@ -279,6 +286,17 @@ dos_status dos_pinned_free(void* ptr);
  * asynchronous on hip_stream.  Hardware traffic counters read for this kernel
  * give the scale of the same counters read for the AdamW kernel. */
 dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
+
+/* Measurement aid: the default launch of dos_adam_step over a device-resident
+ * subgroup with parts taken out -- mode 0 performs only its loads (14 B/param),
+ * mode 1 only its stores (14 B/param; p, m, v and p_lp become 0), mode 2 loads
+ * and stores without the arithmetic (it flips the sign of p, m, v: modes 1 and 2
+ * destroy the optimizer state they run on).  The rates of
+ * modes 0 and 1 are what the memory system reaches in each direction alone; the
+ * AdamW kernel's mixed rate is judged against them.  lds_bytes as in
+ * dos_launch_cfg (0 = the default cap on waves per CU, negative = no cap).
+ * Elements past the last multiple of four are not touched. */
+dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream);
 
 /* Reads one byte of every 4 KiB page of a host buffer and writes it back, with
  * `threads` threads, so that the first host update of a buffer that so far was

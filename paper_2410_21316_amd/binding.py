@@ -31,7 +31,8 @@ class dos_hparams(C.Structure):
 
 
 class dos_launch_cfg(C.Structure):
-    _fields_ = [("variant", C.c_int32), ("block_threads", C.c_int32), ("grid_blocks", C.c_int32)]
+    _fields_ = [("variant", C.c_int32), ("block_threads", C.c_int32), ("grid_blocks", C.c_int32),
+                ("lds_bytes", C.c_int32)]
 
 
 class dos_cost_model(C.Structure):
@@ -93,6 +94,7 @@ SIGNATURES = {
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
     "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "dos_probe_adam_traffic": (C.c_int, [C.POINTER(dos_subgroup), C.c_int32, C.c_int32, C.c_void_p]),
     "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
     "dos_last_hip_error": (C.c_char_p, []),
@@ -170,8 +172,8 @@ def dos_adam_step(sg: dos_subgroup, hp: dos_hparams, stream: int = 0) -> None:
     check(load().dos_adam_step(C.byref(sg), C.byref(hp), C.c_void_p(stream)), "dos_adam_step")
 
 
-def dos_adam_step_cfg(sg, hp, stream=0, variant=0, block_threads=0, grid_blocks=0) -> None:
-    cfg = dos_launch_cfg(variant, block_threads, grid_blocks)
+def dos_adam_step_cfg(sg, hp, stream=0, variant=0, block_threads=0, grid_blocks=0, lds_bytes=0) -> None:
+    cfg = dos_launch_cfg(variant, block_threads, grid_blocks, lds_bytes)
     check(load().dos_adam_step_cfg(C.byref(sg), C.byref(hp), C.c_void_p(stream), C.byref(cfg)),
           "dos_adam_step_cfg")
 
@@ -262,6 +264,11 @@ def dos_pinned_free(ptr: int) -> None:
 
 def dos_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
     check(load().dos_probe_copy(C.c_void_p(dst), C.c_void_p(src), int(nbytes), C.c_void_p(stream)), "dos_probe_copy")
+
+
+def dos_probe_adam_traffic(sg: dos_subgroup, mode: int, stream: int = 0, lds_bytes: int = 0) -> None:
+    check(load().dos_probe_adam_traffic(C.byref(sg), int(mode), int(lds_bytes), C.c_void_p(stream)),
+          "dos_probe_adam_traffic")
 
 
 def dos_host_prefault(ptr: int, nbytes: int, threads: int = 1) -> None:

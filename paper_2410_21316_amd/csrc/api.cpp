@@ -70,6 +70,15 @@ dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, vo
   return dos::launch_probe_copy(dst_dev, src_dev, bytes, hip_stream);
 }
 
+dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream) {
+  dos_status rc = dos::check_subgroup_pointers(sg);
+  if (rc != DOS_OK) return rc;
+  if (mode < 0 || mode > 2) return DOS_EINVAL;
+  if (sg->n == 0) return DOS_OK;
+  if (sg->state_loc != DOS_DEVICE || sg->grad_loc != DOS_DEVICE) return DOS_ESTATE;
+  return dos::launch_probe_traffic(sg, mode, lds_bytes, hip_stream);
+}
+
 dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {
   if (!ptr && bytes) return DOS_EINVAL;
   if (bytes == 0) return DOS_OK;

@@ -43,11 +43,21 @@ def test_ragged_sizes(n, hp):
     run_steps(n, S.BASE_SEED + n, 2, hp, zero_pct=1.0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 0x10, 0x21, 0x32, 0x33])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 0x10, 0x21, 0x32, 0x33, 0x51, 0x73])
 @pytest.mark.parametrize("threads,blocks", [(0, 0), (64, 7), (512, 256), (256, 1)])
 def test_every_launch_shape_gives_the_same_bits(variant, threads, blocks, hp):
     run_steps(300_007, S.BASE_SEED + variant, 2, hp,
               launch=dict(variant=variant, block_threads=threads, grid_blocks=blocks),
+              zero_pct=5.0, heavy_tail=True)
+
+
+@pytest.mark.parametrize("variant", [4, 0x14, 0x24, 0x34, 0x54, 0x74])
+@pytest.mark.parametrize("threads,lds", [(0, 0), (64, -1), (128, 20480), (512, 65536), (256, 1)])
+def test_untiled_layout_and_wave_cap_give_the_same_bits(variant, threads, lds, hp):
+    """The layout without a tile loop (the default of dos_adam_step) under every
+    cache policy, block size and cap on resident waves."""
+    run_steps(300_007, S.BASE_SEED + variant, 2, hp,
+              launch=dict(variant=variant, block_threads=threads, grid_blocks=0, lds_bytes=lds),
               zero_pct=5.0, heavy_tail=True)
 
 
@@ -98,6 +108,10 @@ def test_errors_leave_device_state_untouched(hp):
     good = dos.hparams(step=1, **hp)
     assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
     cfg = dos.dos_launch_cfg(0, 100, 0)
+    assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
+    cfg = dos.dos_launch_cfg(4, 64, 8)          # the untiled layout takes no grid size
+    assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
+    cfg = dos.dos_launch_cfg(1, 64, 0, 65537)   # more LDS than a block may request
     assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
     torch.cuda.synchronize()
     for a, b in zip(before, sg.host_copy()):
