@@ -231,6 +231,9 @@ typedef struct dos_phase_stats {
   uint64_t params_gpu, params_cpu, params_resident;
   int32_t n_gpu, n_cpu, n_resident, n_slots;
   int32_t n_pieces, host_threads;
+  double h2d_span_s, d2h_span_s;  /* first copy start to last copy end per direction
+                                     (DOS_CTX_PROFILE), else -1: span - busy is the
+                                     time a direction sat idle between its copies    */
 } dos_phase_stats;
 
 /* Creates a context: events, worker threads and (unless given) streams.  slot_mem
@@ -267,6 +270,14 @@ dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, c
  * slots, streams and worker threads: pinned copies each way under duplex load,
  * the device kernel over one slot, the host update over the upload ring. */
 dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
+
+/* Timeline of the GPU lane of the context's last phase (contexts created with
+ * DOS_CTX_PROFILE, phases run with a non-NULL stats argument): for each staged piece, in the order they were processed, six
+ * times in milliseconds since the phase's first command -- prefetch start and
+ * end, kernel start and end, flush start and end.  Writes at most max_pieces
+ * rows of six floats into ms6 (a host buffer) and the number of pieces the phase
+ * had into *n_pieces (0 when nothing was timed). */
+dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pieces, int32_t* n_pieces);
 
 /* Replaces the host-update rate and the link rates of `cm` by what the phase that
  * produced `st` actually reached (host lane: parameters / lane time; link: bytes /

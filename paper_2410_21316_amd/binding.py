@@ -66,7 +66,7 @@ class dos_phase_stats(C.Structure):
                 ("cpu_enqueue_s", C.c_double), ("params_gpu", C.c_uint64), ("params_cpu", C.c_uint64),
                 ("params_resident", C.c_uint64), ("n_gpu", C.c_int32), ("n_cpu", C.c_int32),
                 ("n_resident", C.c_int32), ("n_slots", C.c_int32), ("n_pieces", C.c_int32),
-                ("host_threads", C.c_int32)]
+                ("host_threads", C.c_int32), ("h2d_span_s", C.c_double), ("d2h_span_s", C.c_double)]
 
     def asdict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -90,6 +90,7 @@ SIGNATURES = {
                                        C.POINTER(dos_plan), C.POINTER(dos_hparams),
                                        C.POINTER(dos_phase_stats)]),
     "dos_calibrate": (C.c_int, [C.c_void_p, C.POINTER(dos_cost_model)]),
+    "dos_ctx_last_timeline": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]),
     "dos_cost_model_observe": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(dos_phase_stats)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
@@ -301,6 +302,14 @@ class Context:
         check(load().dos_run_update_phase(self._h, arr, n, C.byref(plan.c), C.byref(hp), C.byref(st)),
               "dos_run_update_phase")
         return st
+
+    def dos_ctx_last_timeline(self):
+        """Rows of (prefetch start, end, kernel start, end, flush start, end) in ms, one per staged piece."""
+        n = C.c_int32()
+        check(load().dos_ctx_last_timeline(self._h, None, 0, C.byref(n)), "dos_ctx_last_timeline")
+        buf = (C.c_float * (6 * max(1, n.value)))()
+        check(load().dos_ctx_last_timeline(self._h, buf, n.value, C.byref(n)), "dos_ctx_last_timeline")
+        return [tuple(buf[6 * j:6 * j + 6]) for j in range(n.value)]
 
     def dos_calibrate(self) -> dos_cost_model:
         cm = dos_cost_model()

@@ -6,11 +6,15 @@
 //                 j mod n_slots:  H2D stream: wait(slot free), copy p, m, v (and
 //                 g when it is host-resident) in, record(ready);  compute stream:
 //                 wait(ready), fused AdamW kernel, record(done);  D2H stream:
-//                 wait(done), copy p, m, v back, record(free).  The calling
-//                 thread drives this as a software pipeline with a bounded
-//                 look-ahead (prefetch j+1, then kernel + flush j once j has
-//                 landed); prefetch and flush run full duplex.  Static residents
-//                 (state already in device memory) are updated in place, last.
+//                 wait(done), copy p, m, v back, record(free).  Two threads
+//                 drive this as a software pipeline with a bounded look-ahead:
+//                 the context's prefetch thread enqueues a prefetch as soon as
+//                 its slot is free, the calling thread kernel + flush of piece j
+//                 once j has landed (enqueueing a copy can block the caller
+//                 while earlier copies of that direction are in flight, so each
+//                 direction has its own thread); prefetch and flush run full
+//                 duplex.  Static residents (state already in device memory)
+//                 are updated in place, last.
 //   host lane  -- persistent worker threads take chunks of the CPU-planned
 //                 subgroups, run the host AdamW (which writes the 16-bit
 //                 parameters straight into a pinned ring: the paper's separate
@@ -72,7 +76,11 @@ struct dos_ctx {
   std::vector<std::atomic<int64_t>> ring_seq;  // last chunk index recorded on each ring entry
   // profiling events
   std::vector<hipEvent_t> prof;  // 6 per piece
+  std::vector<float> timeline;   // the last phase's event times, 6 per piece (ms since t0)
   hipEvent_t t0 = nullptr;  // start of the phase on the H2D stream (origin of the profile timeline)
+  // end of the GPU lane: tail[0], tail[1] close the H2D and compute streams, lane_end follows both
+  // and the last flush on the D2H stream; the driver thread sleeps on it
+  hipEvent_t tail[2] = {nullptr, nullptr}, lane_end = nullptr;
   // host workers
   int T = 1;
   std::vector<std::thread> workers;
@@ -92,6 +100,23 @@ struct dos_ctx {
   struct alignas(64) LaneTimes { double compute = 0, wait = 0, enqueue = 0; };
   std::vector<LaneTimes> lane_times;  // one per worker, reset every phase
   std::atomic<bool> cpu_started{false};
+  // prefetch thread of the GPU lane: it enqueues the host-to-device copies, the
+  // calling thread the kernels and the flushes (an enqueue of a copy can block its
+  // caller while earlier copies of the same direction are in flight; with one thread
+  // per direction a blocked prefetch enqueue no longer delays the flushes)
+  std::thread prefetcher;
+  std::mutex pipe_mu;
+  std::condition_variable pipe_cv;
+  uint64_t pf_generation = 0;       // bumped to start a prefetch job
+  bool pf_busy = false;             // a prefetch job is running
+  bool pf_prof = false;             // the job records profile events
+  const dos_subgroup* pf_sgs = nullptr;
+  int64_t pf_enqueued = -1;         // last piece whose prefetch and ready event are enqueued
+  int64_t fl_enqueued = -1;         // last piece whose flush and freed event are enqueued
+  bool pipe_abort = false;          // the calling thread gave up: the prefetcher stops
+  bool pf_quit = false;             // the context is being destroyed
+  hipError_t pf_error = hipSuccess; // first failure of the prefetcher
+  const char* pf_error_what = "";
   // scratch lists reused across phases (reserved at creation)
   std::vector<Chunk> chunks;
   std::vector<Piece> pieces;
@@ -205,12 +230,98 @@ void worker_main(dos_ctx* c, int tid) {
   }
 }
 
+struct SlotPtrs {
+  float *p, *m, *v;
+  uint16_t* g;
+};
+inline SlotPtrs slot_of(const dos_ctx* c, size_t j) {
+  char* base = c->slot_mem + (uint64_t)(j % (size_t)c->n_slots) * c->slot_stride;
+  return SlotPtrs{(float*)base, (float*)(base + 4 * c->slot_params), (float*)(base + 8 * c->slot_params),
+                  (uint16_t*)(base + 12 * c->slot_params)};
+}
+
+// Prefetch of piece j into its slot (H2D stream).  The slot is free once the flush
+// of piece j - n_slots has landed: a host wait, so that no stream ever holds a long
+// chain of blocked commands.  The caller has made sure that flush is enqueued.
+hipError_t prefetch_piece(dos_ctx* c, const dos_subgroup* sgs, const Piece& pc, size_t j, bool prof,
+                          const char** what) {
+  const dos_subgroup& sg = sgs[pc.sg];
+  const int s = (int)(j % (size_t)c->n_slots);
+  const SlotPtrs sl = slot_of(c, j);
+  const size_t fb = pc.cnt * 4;
+  hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
+  hipError_t e = hipSuccess;
+  *what = "hipEventSynchronize";
+  if (j >= (size_t)c->n_slots && (e = hipEventSynchronize(c->freed[s])) != hipSuccess) return e;
+  *what = "hipEventRecord";
+  if (pe && (e = hipEventRecord(pe[0], c->h2d)) != hipSuccess) return e;
+  *what = "prefetch of p";
+  if ((e = hipMemcpyAsync(sl.p, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
+  *what = "prefetch of m";
+  if ((e = hipMemcpyAsync(sl.m, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
+  *what = "prefetch of v";
+  if ((e = hipMemcpyAsync(sl.v, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
+  *what = "prefetch of g";
+  if (sg.grad_loc == DOS_HOST_PINNED &&
+      (e = hipMemcpyAsync(sl.g, sg.g + pc.off, pc.cnt * 2, hipMemcpyHostToDevice, c->h2d)) != hipSuccess)
+    return e;
+  *what = "hipEventRecord";
+  if (pe && (e = hipEventRecord(pe[1], c->h2d)) != hipSuccess) return e;
+  return hipEventRecord(c->ready[s], c->h2d);
+}
+
+void prefetcher_main(dos_ctx* c) {
+  (void)hipSetDevice(c->device);
+  uint64_t seen = 0;
+  for (;;) {
+    {
+      std::unique_lock<std::mutex> lk(c->pipe_mu);
+      c->pipe_cv.wait(lk, [&] { return c->pf_quit || c->pf_generation != seen; });
+      if (c->pf_quit) return;
+      seen = c->pf_generation;
+    }
+    const std::vector<Piece>& pieces = c->pieces;
+    const dos_subgroup* sgs = c->pf_sgs;
+    const bool prof = c->pf_prof;
+    for (size_t j = 0; j < pieces.size(); ++j) {
+      if (j >= (size_t)c->n_slots) {
+        // the flush that frees this slot must have been enqueued before its event means anything
+        std::unique_lock<std::mutex> lk(c->pipe_mu);
+        c->pipe_cv.wait(lk, [&] { return c->pipe_abort || c->fl_enqueued >= (int64_t)(j - (size_t)c->n_slots); });
+        if (c->pipe_abort) break;
+      }
+      const char* what = "";
+      const hipError_t e = prefetch_piece(c, sgs, pieces[j], j, prof, &what);
+      std::lock_guard<std::mutex> lk(c->pipe_mu);
+      if (e != hipSuccess) {
+        c->pf_error = e;
+        c->pf_error_what = what;
+        c->pipe_cv.notify_all();
+        break;
+      }
+      c->pf_enqueued = (int64_t)j;
+      c->pipe_cv.notify_all();
+    }
+    {
+      std::lock_guard<std::mutex> lk(c->pipe_mu);
+      c->pf_busy = false;
+      c->pipe_cv.notify_all();
+    }
+  }
+}
+
 void destroy(dos_ctx* c) {
   {
     std::lock_guard<std::mutex> lk(c->mu);
     c->quit = true;
   }
   c->cv_start.notify_all();
+  {
+    std::lock_guard<std::mutex> lk(c->pipe_mu);
+    c->pf_quit = true;
+    c->pipe_cv.notify_all();
+  }
+  if (c->prefetcher.joinable()) c->prefetcher.join();
   for (auto& t : c->workers) t.join();
   (void)hipSetDevice(c->device);
   for (int s = 0; s < kMaxSlots; ++s) {
@@ -223,6 +334,8 @@ void destroy(dos_ctx* c) {
   for (auto e : c->prof)
     if (e) (void)hipEventDestroy(e);
   if (c->t0) (void)hipEventDestroy(c->t0);
+  for (hipEvent_t e : {c->tail[0], c->tail[1], c->lane_end})
+    if (e) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -314,8 +427,13 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
   for (int r = 0; r < ring_n; ++r)
     if ((e = hipEventCreateWithFlags(&c->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
   if ((e = hipEventCreate(&c->t0)) != hipSuccess) return fail(e, "hipEventCreate");
+  for (hipEvent_t* ev : {&c->tail[0], &c->tail[1]})
+    if ((e = hipEventCreateWithFlags(ev, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+  if ((e = hipEventCreateWithFlags(&c->lane_end, hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
+    return fail(e, "hipEventCreate");
   if (c->flags & DOS_CTX_PROFILE) {
     c->prof.assign((size_t)kProfPieces * 6, nullptr);
+    c->timeline.reserve((size_t)kProfPieces * 6);
     for (auto& ev : c->prof)
       if ((e = hipEventCreate(&ev)) != hipSuccess) return fail(e, "hipEventCreate");
   }
@@ -324,6 +442,7 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
   c->lane_times.resize(c->T);
   c->workers.reserve(c->T);
   for (int t = 0; t < c->T; ++t) c->workers.emplace_back(worker_main, c, t);
+  if (c->n_slots > 0) c->prefetcher = std::thread(prefetcher_main, c);
   *out = c;
   return DOS_OK;
 }
@@ -414,42 +533,12 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
   auto enqueue_gpu = [&]() -> dos_status {
     HIP_TRY(c, hipEventRecord(c->t0, c->h2d), "hipEventRecord");
     // the other streams start no earlier than t0 (keeps the timeline comparable)
-    struct SlotPtrs {
-      float *p, *m, *v;
-      uint16_t* g;
-    };
-    auto slot_of = [&](size_t j) {
-      char* base = c->slot_mem + (uint64_t)(j % (size_t)c->n_slots) * c->slot_stride;
-      return SlotPtrs{(float*)base, (float*)(base + 4 * c->slot_params), (float*)(base + 8 * c->slot_params),
-                      (uint16_t*)(base + 12 * c->slot_params)};
-    };
-    // prefetch of piece j into its slot (H2D stream)
-    auto enqueue_prefetch = [&](size_t j) -> dos_status {
-      const Piece& pc = pieces[j];
-      const dos_subgroup& sg = sgs[pc.sg];
-      const int s = (int)(j % (size_t)c->n_slots);
-      const SlotPtrs sl = slot_of(j);
-      const size_t fb = pc.cnt * 4;
-      hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
-      // the slot is free once the flush of piece j - n_slots has landed (host wait:
-      // no stream ever holds a long chain of blocked commands)
-      if (j >= (size_t)c->n_slots) HIP_TRY(c, hipEventSynchronize(c->freed[s]), "hipEventSynchronize");
-      if (pe) HIP_TRY(c, hipEventRecord(pe[0], c->h2d), "hipEventRecord");
-      HIP_TRY(c, hipMemcpyAsync(sl.p, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of p");
-      HIP_TRY(c, hipMemcpyAsync(sl.m, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of m");
-      HIP_TRY(c, hipMemcpyAsync(sl.v, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d), "prefetch of v");
-      if (sg.grad_loc == DOS_HOST_PINNED)
-        HIP_TRY(c, hipMemcpyAsync(sl.g, sg.g + pc.off, pc.cnt * 2, hipMemcpyHostToDevice, c->h2d), "prefetch of g");
-      if (pe) HIP_TRY(c, hipEventRecord(pe[1], c->h2d), "hipEventRecord");
-      HIP_TRY(c, hipEventRecord(c->ready[s], c->h2d), "hipEventRecord");
-      return DOS_OK;
-    };
     // kernel over the slot (compute stream) and flush back to the host (D2H stream)
     auto enqueue_update_and_flush = [&](size_t j) -> dos_status {
       const Piece& pc = pieces[j];
       const dos_subgroup& sg = sgs[pc.sg];
       const int s = (int)(j % (size_t)c->n_slots);
-      const SlotPtrs sl = slot_of(j);
+      const SlotPtrs sl = slot_of(c, j);
       const size_t fb = pc.cnt * 4;
       hipEvent_t* pe = prof ? &c->prof[j * 6] : nullptr;
       const uint16_t* gdev = (sg.grad_loc == DOS_HOST_PINNED) ? sl.g : sg.g + pc.off;
@@ -471,28 +560,55 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       HIP_TRY(c, hipEventRecord(c->freed[s], c->d2h), "hipEventRecord");
       return DOS_OK;
     };
-    // Software pipeline driven by the calling thread.  The prefetch of piece j+1
-    // is enqueued before the flush of piece j, and the flush only once piece j
-    // has landed: when the D2H stream submits a copy, the DMA engine that serves
-    // the prefetches is busy, so the runtime (which picks a free engine per
-    // stream at submission time) never puts both directions on one engine.
+    // Software pipeline driven by two threads.  The prefetch thread enqueues the
+    // prefetch of piece j as soon as its slot is free (the flush of piece
+    // j - n_slots has landed); this thread enqueues kernel and flush of piece j
+    // once piece j has landed.  Prefetches therefore run at most n_slots - 1
+    // pieces ahead, and when the D2H stream submits a copy the DMA engine that
+    // serves the prefetches is busy, so the runtime (which picks a free engine
+    // per stream at submission time) never puts both directions on one engine.
     const size_t np = pieces.size();
     if (np > 0) {
-      dos_status r = enqueue_prefetch(0);
-      if (r != DOS_OK) return r;
-    }
-    for (size_t j = 0; j < np; ++j) {
-      if (c->n_slots >= 2 && j + 1 < np) {
-        dos_status r = enqueue_prefetch(j + 1);
-        if (r != DOS_OK) return r;
+      {
+        std::lock_guard<std::mutex> lk(c->pipe_mu);
+        c->pf_sgs = sgs;
+        c->pf_prof = prof;
+        c->pf_enqueued = c->fl_enqueued = -1;
+        c->pipe_abort = false;
+        c->pf_error = hipSuccess;
+        c->pf_busy = true;
+        ++c->pf_generation;
       }
-      HIP_TRY(c, hipEventSynchronize(c->ready[j % (size_t)c->n_slots]), "hipEventSynchronize");
-      dos_status r = enqueue_update_and_flush(j);
-      if (r != DOS_OK) return r;
-      if (c->n_slots < 2 && j + 1 < np) {  // one slot: strictly serial
-        r = enqueue_prefetch(j + 1);
-        if (r != DOS_OK) return r;
+      c->pipe_cv.notify_all();
+      dos_status r = DOS_OK;
+      for (size_t j = 0; j < np && r == DOS_OK; ++j) {
+        {
+          std::unique_lock<std::mutex> lk(c->pipe_mu);
+          c->pipe_cv.wait(lk, [&] { return c->pf_error != hipSuccess || c->pf_enqueued >= (int64_t)j; });
+          if (c->pf_error != hipSuccess) {
+            dos::note_hip_error((int)c->pf_error, c->pf_error_what);
+            c->sticky = r = DOS_EHIP;
+            break;
+          }
+        }
+        r = [&]() -> dos_status {
+          HIP_TRY(c, hipEventSynchronize(c->ready[j % (size_t)c->n_slots]), "hipEventSynchronize");
+          return enqueue_update_and_flush(j);
+        }();
+        if (r == DOS_OK) {
+          std::lock_guard<std::mutex> lk(c->pipe_mu);
+          c->fl_enqueued = (int64_t)j;
+          c->pipe_cv.notify_all();
+        }
       }
+      {
+        // the prefetch thread is idle again before anything else touches the H2D stream
+        std::unique_lock<std::mutex> lk(c->pipe_mu);
+        if (r != DOS_OK) c->pipe_abort = true;
+        c->pipe_cv.notify_all();
+        c->pipe_cv.wait(lk, [&] { return !c->pf_busy; });
+      }
+      if (r != DOS_OK) return r;
     }
     // static residents, placed last: their kernels overlap the tail transfers
     for (int k = 0; k < n_sg; ++k) {
@@ -505,11 +621,20 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
         return kr;
       }
     }
+    // the lane ends when all three streams have drained: one event behind all of them
+    HIP_TRY(c, hipEventRecord(c->tail[0], c->h2d), "hipEventRecord");
+    HIP_TRY(c, hipEventRecord(c->tail[1], c->comp), "hipEventRecord");
+    HIP_TRY(c, hipStreamWaitEvent(c->d2h, c->tail[0], 0), "hipStreamWaitEvent");
+    HIP_TRY(c, hipStreamWaitEvent(c->d2h, c->tail[1], 0), "hipStreamWaitEvent");
+    HIP_TRY(c, hipEventRecord(c->lane_end, c->d2h), "hipEventRecord");
     return DOS_OK;
   };
   gpu_rc = enqueue_gpu();
 
-  // ---- join: host lane first (it keeps enqueueing uploads), then the streams
+  // ---- join: the GPU lane (asleep on its last event, so that the lane's own end is
+  // timed and no core is taken from the workers), the host lane, then the streams
+  hipError_t e0 = gpu_rc == DOS_OK ? hipEventSynchronize(c->lane_end) : hipSuccess;
+  const auto t_gpu_done = clk::now();
   if (!chunks.empty()) {
     std::unique_lock<std::mutex> lk(c->mu);
     c->cv_done.wait(lk, [&] { return c->running == 0; });
@@ -517,11 +642,10 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
   hipError_t e1 = hipStreamSynchronize(c->h2d);
   hipError_t e2 = hipStreamSynchronize(c->comp);
   hipError_t e3 = hipStreamSynchronize(c->d2h);
-  const auto t_gpu_done = clk::now();
   hipError_t e4 = hipStreamSynchronize(c->upl);
   const auto t_exit = clk::now();
   if (gpu_rc != DOS_OK) return gpu_rc;
-  for (hipError_t e : {e1, e2, e3, e4})
+  for (hipError_t e : {e0, e1, e2, e3, e4})
     if (e != hipSuccess) {
       dos::note_hip_error((int)e, "hipStreamSynchronize at the end of the update phase");
       (void)hipGetLastError();
@@ -541,6 +665,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       if (sgs[pc.sg].grad_loc == DOS_HOST_PINNED) stats->h2d_bytes += 2.0 * (double)pc.cnt;
     stats->d2h_bytes = 12.0 * (double)params_gpu;
     stats->h2d_busy_s = stats->d2h_busy_s = stats->gpu_busy_s = stats->duplex_overlap_s = -1.0;
+    stats->h2d_span_s = stats->d2h_span_s = -1.0;
     stats->cpu_lane_s = chunks.empty() ? 0.0 : secs(c->cpu_first, c->cpu_last);
     stats->gpu_lane_s = secs(t_entry, t_gpu_done);
     stats->params_gpu = params_gpu;
@@ -558,6 +683,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
         stats->cpu_wait_s += lt.wait;
         stats->cpu_enqueue_s += lt.enqueue;
       }
+    c->timeline.clear();
     if (prof && !pieces.empty()) {
       std::vector<std::pair<double, double>> up, down;
       double hb = 0, db = 0, gb = 0;
@@ -576,15 +702,28 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
         db += (t[5] - t[4]) * 1e-3;
         up.emplace_back(t[0] * 1e-3, t[1] * 1e-3);
         down.emplace_back(t[4] * 1e-3, t[5] * 1e-3);
+        c->timeline.insert(c->timeline.end(), t, t + 6);
       }
+      if (!ok) c->timeline.clear();
       if (ok) {
         stats->h2d_busy_s = hb;
         stats->d2h_busy_s = db;
         stats->gpu_busy_s = gb;
         stats->duplex_overlap_s = overlap_of_unions(up, down);
+        stats->h2d_span_s = up.back().second - up.front().first;
+        stats->d2h_span_s = down.back().second - down.front().first;
       }
     }
   }
+  return DOS_OK;
+}
+
+extern "C" dos_status dos_ctx_last_timeline(const dos_ctx* c, float* ms6, int32_t max_pieces, int32_t* n_pieces) {
+  if (!c || !n_pieces || max_pieces < 0 || (max_pieces > 0 && !ms6)) return DOS_EINVAL;
+  const size_t have = c->timeline.size() / 6;
+  *n_pieces = (int32_t)have;
+  const size_t take = std::min(have, (size_t)max_pieces);
+  if (take) memcpy(ms6, c->timeline.data(), take * 6 * sizeof(float));
   return DOS_OK;
 }
 

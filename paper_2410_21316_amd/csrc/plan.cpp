@@ -236,10 +236,24 @@ extern "C" dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase
   if (!cm || !st) return DOS_EINVAL;
   if (st->params_cpu > 0 && st->cpu_lane_s > 0.0) cm->cpu_params_per_s = (double)st->params_cpu / st->cpu_lane_s;
   if (st->params_gpu > 0 && st->h2d_busy_s > 0.0 && st->d2h_busy_s > 0.0) {
-    // summed copy durations (DOS_CTX_PROFILE) give the rate each direction reached while busy
-    const double staged = st->h2d_bytes - 2.0 * (double)st->params_cpu;  // bytes the prefetches moved
-    cm->h2d_Bps = staged / st->h2d_busy_s;
+    // summed copy durations (DOS_CTX_PROFILE) give the rate each direction reached while busy.
+    // The 16-bit uploads of the host lane share the host-to-device direction with the
+    // prefetches and the cost model charges them to it, so the bytes they moved while
+    // prefetches were running count towards its rate (uploads are spread evenly over the
+    // host lane).
+    const double uploads = 2.0 * (double)st->params_cpu;
+    const double staged = st->h2d_bytes - uploads;  // bytes the prefetches moved
+    const double share = st->cpu_lane_s > 0.0 ? std::min(1.0, st->h2d_busy_s / st->cpu_lane_s) : 0.0;
+    cm->h2d_Bps = (staged + uploads * share) / st->h2d_busy_s;
     cm->d2h_Bps = st->d2h_bytes / st->d2h_busy_s;
+    // The lane as a whole may have run longer than its busier direction explains
+    // (a direction idles while it waits for the other one's piece): both rates are
+    // lowered so that the model reproduces the lane time of the phase it was fed.
+    const double lane = std::max(st->h2d_bytes / cm->h2d_Bps, st->d2h_bytes / cm->d2h_Bps);
+    if (st->gpu_lane_s > lane && lane > 0.0) {
+      cm->h2d_Bps *= lane / st->gpu_lane_s;
+      cm->d2h_Bps *= lane / st->gpu_lane_s;
+    }
   } else if (st->params_gpu > 0 && st->gpu_lane_s > 0.0 && st->d2h_bytes > 0.0) {
     // without per-copy timing: the lane as a whole bounds both directions
     const double rate = st->d2h_bytes / st->gpu_lane_s;

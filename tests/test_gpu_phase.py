@@ -148,11 +148,24 @@ def test_transfers_overlap_full_duplex(hp):
     try:
         for step in (1, 2):
             stats = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp))
+        timeline = ctx.dos_ctx_last_timeline()
     finally:
         ctx.close()
         ctx._keep[1].free()
         state.free()
     assert stats.n_pieces == 12
+    # the per-piece timeline: prefetch, kernel and flush of a piece follow each other, pieces of one
+    # direction do not overlap, a slot is refilled only after its flush, and the spans cover the busy times
+    assert len(timeline) == 12
+    for j, (p0, p1, k0, k1, f0, f1) in enumerate(timeline):
+        assert 0.0 <= p0 < p1 <= k0 < k1 <= f0 < f1, (j, timeline[j])
+        if j:
+            assert timeline[j - 1][1] <= p0 and timeline[j - 1][5] <= f0
+        if j >= 3:
+            assert timeline[j - 3][5] <= p0, "slot refilled before its flush had landed"
+    assert stats.h2d_span_s == pytest.approx((timeline[-1][1] - timeline[0][0]) * 1e-3, rel=1e-3)
+    assert stats.h2d_span_s >= stats.h2d_busy_s * 0.999 and stats.d2h_span_s >= stats.d2h_busy_s * 0.999
+    assert stats.gpu_lane_s >= stats.d2h_span_s
     print({k: v for k, v in stats.asdict().items() if k.endswith("_s")})
     # a good part of the flush time runs concurrently with prefetches
     assert stats.duplex_overlap_s > stats.d2h_busy_s / 4 > 0.0

@@ -217,12 +217,30 @@ def test_cost_model_observe_takes_the_measured_rates():
     st.params_gpu = 1_300_000_000
     st.h2d_bytes = 12.0 * st.params_gpu + 2.0 * st.params_cpu
     st.d2h_bytes = 12.0 * st.params_gpu
-    st.h2d_busy_s, st.d2h_busy_s, st.gpu_lane_s = 0.40, 0.43, 0.46
+    st.h2d_busy_s, st.d2h_busy_s, st.gpu_lane_s = 0.40, 0.43, 0.43
     dos.dos_cost_model_observe(cm, st)
     assert cm.cpu_params_per_s == pytest.approx(8e9)
-    assert cm.h2d_Bps == pytest.approx(12.0 * 1.3e9 / 0.40)
+    # prefetch bytes plus the share of the 16-bit uploads that ran while prefetches were busy
+    assert cm.h2d_Bps == pytest.approx((12.0 * 1.3e9 + 2.0 * 3.6e9 * (0.40 / 0.45)) / 0.40)
     assert cm.d2h_Bps == pytest.approx(12.0 * 1.3e9 / 0.43)
     assert cm.gpu_params_per_s == 200e9
+    # the model is then consistent with the phase it was taken from: the host-to-device time it
+    # predicts for the same plan is the time that direction was busy, stretched to the host lane
+    assert (st.h2d_bytes / cm.h2d_Bps) == pytest.approx(0.40 * st.h2d_bytes / (12.0 * 1.3e9 + 7.2e9 * 0.40 / 0.45))
+    # uploads never outlast the host lane: a prefetch stream busier than the host lane gets all of them
+    cm1 = dos.cost_model(56e9, 48e9, 200e9, 8e9)
+    st.h2d_busy_s = 0.50
+    dos.dos_cost_model_observe(cm1, st)
+    assert cm1.h2d_Bps == pytest.approx(st.h2d_bytes / 0.50)
+    st.h2d_busy_s = 0.40
+    # a lane that ran longer than its busier direction explains lowers both rates by the same factor,
+    # so that the model gives back the lane time it was fed
+    cm4 = dos.cost_model(56e9, 48e9, 200e9, 8e9)
+    st.gpu_lane_s = 0.50
+    dos.dos_cost_model_observe(cm4, st)
+    assert max(st.h2d_bytes / cm4.h2d_Bps, st.d2h_bytes / cm4.d2h_Bps) == pytest.approx(0.50)
+    assert cm4.h2d_Bps / cm4.d2h_Bps == pytest.approx(cm.h2d_Bps / cm.d2h_Bps)
+    st.gpu_lane_s = 0.46
     # without per-copy timing only an upper bound on the time is known: rates may only drop
     cm2 = dos.cost_model(56e9, 48e9, 200e9, 8e9)
     st.h2d_busy_s = st.d2h_busy_s = -1.0
