@@ -48,6 +48,10 @@ def _bind(lib):
     lib.ref_adamw_step.restype = ctypes.c_int
     lib.ref_adamw_step_parallel.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64, *hp, ctypes.c_int]
     lib.ref_adamw_step_parallel.restype = ctypes.c_int
+    lib.ref_adagrad_step.argtypes = [f32p, f32p, u16p, u16p, ctypes.c_uint64] + [ctypes.c_float] * 3 + [ctypes.c_int]
+    lib.ref_adagrad_step.restype = ctypes.c_int
+    lib.ref_rmsprop_step.argtypes = [f32p, f32p, u16p, u16p, ctypes.c_uint64] + [ctypes.c_float] * 4 + [ctypes.c_int]
+    lib.ref_rmsprop_step.restype = ctypes.c_int
     lib.ref_adamw_scalars.argtypes = [*hp, f32p]
     lib.ref_adamw_scalars.restype = None
     lib.ref_bf16_to_f32_n.argtypes = [u16p, f32p, ctypes.c_uint64]
@@ -94,6 +98,45 @@ def adamw_step(p, m, v, g, p_lp, *, lr, beta1, beta2, eps, weight_decay, step, t
     if rc < 0:
         raise ValueError("AdamW is not defined for these hyper-parameters / step")
     return used
+
+
+def adagrad_step(p, v, g, p_lp, *, lr, eps, weight_decay, threads=1):
+    """Adagrad over ``p`` and its accumulator ``v`` (float32 numpy, in place) with
+    bf16 gradient bits ``g``; writes the bf16 bits of the new parameters into
+    ``p_lp``.  Returns the number of threads used (``threads`` as in adamw_step)."""
+    n = p.shape[0]
+    assert p.ndim == 1 and v.shape == g.shape == p_lp.shape == (n,)
+    used = _load().ref_adagrad_step(_f32(p), _f32(v), _u16(g, False), _u16(p_lp, True), n, lr, eps, weight_decay,
+                                    int(threads))
+    if used < 0:
+        raise ValueError("Adagrad is not defined for these hyper-parameters")
+    return used
+
+
+def rmsprop_step(p, v, g, p_lp, *, lr, alpha, eps, weight_decay, threads=1):
+    """RMSProp (uncentred, no momentum) over ``p`` and its running mean of squared
+    gradients ``v``; arguments as adagrad_step plus the smoothing constant."""
+    n = p.shape[0]
+    assert p.ndim == 1 and v.shape == g.shape == p_lp.shape == (n,)
+    used = _load().ref_rmsprop_step(_f32(p), _f32(v), _u16(g, False), _u16(p_lp, True), n, lr, alpha, eps,
+                                    weight_decay, int(threads))
+    if used < 0:
+        raise ValueError("RMSProp is not defined for these hyper-parameters")
+    return used
+
+
+def optimizer_step(name, p, m, v, g, p_lp, *, lr, beta1, beta2, eps, weight_decay, step, threads=1):
+    """One step of the named rule ("adamw", "adagrad", "rmsprop") with the
+    hyper-parameter set of adamw_step: Adagrad ignores the betas and the step,
+    RMSProp takes beta2 as its smoothing constant; neither touches ``m``."""
+    if name == "adamw":
+        return adamw_step(p, m, v, g, p_lp, lr=lr, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay,
+                          step=step, threads=threads)
+    if name == "adagrad":
+        return adagrad_step(p, v, g, p_lp, lr=lr, eps=eps, weight_decay=weight_decay, threads=threads)
+    if name == "rmsprop":
+        return rmsprop_step(p, v, g, p_lp, lr=lr, alpha=beta2, eps=eps, weight_decay=weight_decay, threads=threads)
+    raise ValueError(name)
 
 
 def scalars(*, lr, beta1, beta2, eps, weight_decay, step) -> dict:

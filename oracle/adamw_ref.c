@@ -27,6 +27,11 @@
  * independent double-precision evaluation of the textbook formulas, torch's
  * AdamW, element independence by brute force, and an exhaustive check of the
  * bf16 helpers.
+ *
+ * The end of the file holds the two other adaptive optimizers that Section 4.1
+ * names as equally parallel, Adagrad and RMSProp, in the same mixed-precision
+ * setting (FP32 p and one FP32 accumulator v, 16-bit gradients in, 16-bit
+ * parameters out); their definitions and pins are stated there.
  */
 #include <math.h>
 #include <stdint.h>
@@ -153,6 +158,116 @@ int ref_adamw_step_parallel(float* p, float* m, float* v, const uint16_t* g, uin
 #else
   (void)threads;
   for (uint64_t i = 0; i < n; ++i) ref_adamw_element(&s, &p[i], &m[i], &v[i], g[i], &p_lp[i]);
+#endif
+  return used;
+}
+
+/* ---------------------------------------------------------------------------
+ * Adagrad and RMSProp.  Section 4.1 of the paper lists them next to Adam as
+ * adaptive optimizers whose update is independent per element; it gives no
+ * equations, so these are the textbook rules, with the same decoupled weight
+ * decay, eps placement (outside the root) and 16-bit copy as the AdamW above.
+ * The state is p and one accumulator v; there is no first moment and no bias
+ * correction, so the step index does not enter.
+ *
+ *   Adagrad (Duchi, Hazan, Singer), diagonal form:
+ *       v_t = v + g*g
+ *       p_t = p*(1 - lr*wd) - lr * g / (sqrt(v_t) + eps)
+ *   RMSProp (the uncentred, momentum-free form):
+ *       v_t = alpha*v + (1-alpha)*g*g
+ *       p_t = p*(1 - lr*wd) - lr * g / (sqrt(v_t) + eps)
+ *
+ * Pins (tests/test_oracle_pins.py): first step from v = 0 (sign step, scaled by
+ * 1/sqrt(1-alpha) for RMSProp), constant gradients (v_T = T g^2 and the
+ * harmonic-root sum for Adagrad; v_t = g^2 (1-alpha^t) for RMSProp), pure decay
+ * for zero gradients, an independent double-precision evaluation, torch's
+ * Adagrad and RMSprop, element independence.
+ */
+static inline void ref_accum_tail(float lr, float eps, float decay, float g, float vt, float* p,
+                                  float* v, uint16_t* p_lp) {
+  float r = sqrtf(vt);
+  float d = r + eps;
+  float pd = *p * decay;             /* decoupled decay acts on the old p */
+  float u = g / d;
+  float w = lr * u;
+  float pt = pd - w;
+  *v = vt;
+  *p = pt;
+  *p_lp = ref_f32_to_bf16(pt);
+}
+
+static inline void ref_adagrad_element(float lr, float eps, float decay, float* p, float* v,
+                                       uint16_t g16, uint16_t* p_lp) {
+  float g = ref_bf16_to_f32(g16);
+  float f = g * g;
+  float vt = *v + f;
+  ref_accum_tail(lr, eps, decay, g, vt, p, v, p_lp);
+}
+
+static inline void ref_rmsprop_element(float lr, float alpha, float oma, float eps, float decay,
+                                       float* p, float* v, uint16_t g16, uint16_t* p_lp) {
+  float g = ref_bf16_to_f32(g16);
+  float c = alpha * *v;
+  float e = oma * g;
+  float f = e * g;
+  float vt = c + f;
+  ref_accum_tail(lr, eps, decay, g, vt, p, v, p_lp);
+}
+
+/* Update n elements in place.  threads == 1: the plain scalar loop; otherwise
+ * the same body under a static parallel-for (threads < 1: all cores).  Returns
+ * the number of threads used, or -1 for arguments the update is not defined for
+ * (negative eps). */
+int ref_adagrad_step(float* p, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n, float lr,
+                     float eps, float weight_decay, int threads) {
+  if (!(eps >= 0.0f)) return -1;
+  const float decay = (float)(1.0 - (double)lr * (double)weight_decay);
+  int used = 1;
+  if (threads == 1) {
+    for (uint64_t i = 0; i < n; ++i) ref_adagrad_element(lr, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
+    return 1;
+  }
+#ifdef _OPENMP
+  if (threads < 1) threads = omp_get_max_threads();
+#pragma omp parallel num_threads(threads)
+  {
+#pragma omp single
+    used = omp_get_num_threads();
+#pragma omp for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i)
+      ref_adagrad_element(lr, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
+  }
+#else
+  for (uint64_t i = 0; i < n; ++i) ref_adagrad_element(lr, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
+#endif
+  return used;
+}
+
+/* As above; also -1 for alpha outside [0, 1). */
+int ref_rmsprop_step(float* p, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n, float lr,
+                     float alpha, float eps, float weight_decay, int threads) {
+  if (!(eps >= 0.0f) || !(alpha >= 0.0f && alpha < 1.0f)) return -1;
+  const float decay = (float)(1.0 - (double)lr * (double)weight_decay);
+  const float oma = 1.0f - alpha;
+  int used = 1;
+  if (threads == 1) {
+    for (uint64_t i = 0; i < n; ++i)
+      ref_rmsprop_element(lr, alpha, oma, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
+    return 1;
+  }
+#ifdef _OPENMP
+  if (threads < 1) threads = omp_get_max_threads();
+#pragma omp parallel num_threads(threads)
+  {
+#pragma omp single
+    used = omp_get_num_threads();
+#pragma omp for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i)
+      ref_rmsprop_element(lr, alpha, oma, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
+  }
+#else
+  for (uint64_t i = 0; i < n; ++i)
+    ref_rmsprop_element(lr, alpha, oma, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);
 #endif
   return used;
 }

@@ -9,6 +9,7 @@ import subprocess
 import pytest
 
 import test_oracle_pins as pins
+import test_oracle_pins_accum as acc
 from oracle import adamw_oracle as ref
 
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "adamw_ref.c")
@@ -30,6 +31,21 @@ PIN_CHECKS = [
     pins.test_bf16_widening_is_exact_and_roundtrips_exhaustively,
     pins.test_bf16_rounding_hand_built_cases,
     pins.test_bf16_rounding_is_nearest_value_with_even_ties,
+    # Adagrad and RMSProp
+    lambda: acc.test_adagrad_first_step_is_sign_step(0.3),
+    lambda: acc.test_rmsprop_first_step_is_scaled_sign_step(0.3),
+    lambda: acc.test_adagrad_constant_gradient(-7e-4),
+    lambda: acc.test_rmsprop_constant_gradient(3e-3),
+    lambda: acc.test_zero_gradients_give_pure_decoupled_decay("adagrad"),
+    lambda: acc.test_zero_gradients_give_pure_decoupled_decay("rmsprop"),
+    lambda: acc.test_eps_sits_outside_the_root("adagrad"),
+    lambda: acc.test_eps_sits_outside_the_root("rmsprop"),
+    lambda: acc.test_against_double_precision_textbook("adagrad", 1e-5, 0.2, 3e-3),
+    lambda: acc.test_against_double_precision_textbook("rmsprop", 1e-3, 0.0, 1e-2),
+    lambda: acc.test_against_torch("adagrad"),
+    lambda: acc.test_against_torch("rmsprop"),
+    lambda: acc.test_elements_are_independent_and_loops_agree("adagrad"),
+    lambda: acc.test_elements_are_independent_and_loops_agree("rmsprop"),
 ]
 
 # (name, [(text in the reference, planted replacement), ...])
@@ -72,6 +88,33 @@ MUTANTS = [
     ("low-precision copy of the old parameter", [("*p_lp = ref_f32_to_bf16(pt);", "*p_lp = ref_f32_to_bf16(pd);")]),
     ("parallel loop skips the last element", [("for (int64_t i = 0; i < (int64_t)n; ++i)",
                                                "for (int64_t i = 0; i < (int64_t)n - 1; ++i)")]),
+    # Adagrad and RMSProp
+    ("adagrad: gradient not squared", [("float f = g * g;", "float f = g;")]),
+    ("adagrad: accumulator overwritten", [("float vt = *v + f;", "float vt = f;")]),
+    ("adagrad: accumulator decreases", [("float vt = *v + f;", "float vt = *v - f;")]),
+    ("accumulators: eps dropped", [("float d = r + eps;", "float d = r;")]),
+    ("accumulators: eps inside the root", [("float r = sqrtf(vt);\n  float d = r + eps;",
+                                            "float r = sqrtf(vt + eps);\n  float d = r;")]),
+    ("accumulators: quotient transposed", [("float u = g / d;", "float u = d / g;")]),
+    ("accumulators: learning rate dropped", [("float w = lr * u;", "float w = u;")]),
+    ("accumulators: update added", [("float pt = pd - w;\n  *v = vt;", "float pt = pd + w;\n  *v = vt;")]),
+    ("accumulators: weight decay dropped", [("float pd = *p * decay;", "float pd = *p;")]),
+    ("accumulators: new accumulator not stored", [("float pt = pd - w;\n  *v = vt;", "float pt = pd - w;")]),
+    ("accumulators: 16-bit copy of the decayed old parameter",
+     [("*p = pt;\n  *p_lp = ref_f32_to_bf16(pt);\n}\n\nstatic inline void ref_adagrad_element",
+       "*p = pt;\n  *p_lp = ref_f32_to_bf16(pd);\n}\n\nstatic inline void ref_adagrad_element")]),
+    ("adagrad: decay without the learning rate",
+     [("const float decay = (float)(1.0 - (double)lr * (double)weight_decay);",
+       "const float decay = (float)(1.0 - (double)weight_decay);")]),
+    ("adagrad: gradient index reversed",
+     [("ref_adagrad_element(lr, eps, decay, &p[i], &v[i], g[i], &p_lp[i]);\n    return 1;",
+       "ref_adagrad_element(lr, eps, decay, &p[i], &v[i], g[n - 1 - i], &p_lp[i]);\n    return 1;")]),
+    ("rmsprop: old mean not discounted", [("float c = alpha * *v;", "float c = *v;")]),
+    ("rmsprop: new term weighted by alpha", [("const float oma = 1.0f - alpha;", "const float oma = alpha;")]),
+    ("rmsprop: gradient not squared", [("float e = oma * g;\n  float f = e * g;", "float e = oma * g;\n  float f = e;")]),
+    ("rmsprop: parallel loop skips the last element",
+     [("for (int64_t i = 0; i < (int64_t)n; ++i)\n      ref_rmsprop_element",
+       "for (int64_t i = 0; i < (int64_t)n - 1; ++i)\n      ref_rmsprop_element")]),
 ]
 
 
