@@ -9,7 +9,7 @@ workloads ride in the same line under "extra": the 7B-parameter resident state
 (70 x 100M) and the 13B-parameter host-offloaded state (130 x 100M, 40 GB GPU
 budget) run through dos_plan_subgroups + dos_run_update_phase.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4|none] [--ablation] [--sweep] [--full-size]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,rules|none] [--ablation] [--sweep] [--full-size]
 """
 from __future__ import annotations
 
@@ -43,13 +43,13 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def timed_resident(state, dos, torch, hp_kw, steps, warmup, stream):
+def timed_resident(state, dos, torch, hp_kw, steps, warmup, stream, optimizer="adamw"):
     """W warm-up steps then exactly K timed steps; returns (wall_s, event_s, launches)."""
     sh = stream.cuda_stream
     n_sets = state.n_grad_sets
 
     def one_step(step):
-        h = dos.hparams(step=step, **hp_kw)
+        h = dos.hparams(step=step, optimizer=optimizer, **hp_kw)
         for sg in state.descs[(step - 1) % n_sets]:
             dos.dos_adam_step(sg, h, sh)
 
@@ -172,6 +172,58 @@ def bench_c2(args, dos, torch, np):
     del state
     torch.cuda.empty_cache()
     return res
+
+
+def bench_other_rules(args, dos, torch, np):
+    """Adagrad and RMSProp (the other adaptive optimizers the paper's Section 4.1 names) on the c2 shape:
+    p and one accumulator, 20 bytes per parameter (reads 4+4+2, writes 4+4+2); whole state compared with
+    the oracle's rule of the same name."""
+    from paper_2410_21316_amd import workloads as W
+    import dos_synth as S
+    from oracle import adamw_oracle as ref
+    hp_kw = dict(S.HPARAMS)
+    sizes = [31_000_000] * 4
+    n_sets = 4
+    out = {}
+    for rule in ("adagrad", "rmsprop"):
+        state = W.ResidentState(sizes, S.BASE_SEED + 3, "cuda:0", n_grad_sets=n_sets)
+        for k in range(n_sets):
+            state.fill_grads(k, k + 1, zero_pct=1.0)
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        wall, ev_s, launches = timed_resident(state, dos, torch, hp_kw, args.steps, args.warmup, stream, rule)
+        value = state.total * args.steps / wall
+        launch_s = ev_s / launches
+        r = {"params_per_s": value, "ms_per_step": wall / args.steps * 1e3, "bytes_per_param": 20,
+             "kernel_avg_launch_us": launch_s * 1e6, "kernel_GBps": 20 * sizes[0] / launch_s / 1e9,
+             "hbm_frac_of_peak": 20 * sizes[0] / launch_s / 1e9 / HBM_PEAK_GBPS}
+        if not args.no_cpu_baseline:
+            bad = 0
+            t_or = 0.0
+            for i, n in enumerate(sizes):
+                p = torch.empty(n, dtype=torch.float32, device="cuda:0")
+                S.fill_chunked(lambda start, count: S.params(state.seed, i, start, count, "cuda:0"), p)
+                want = [p.cpu().numpy(), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)]
+                del p
+                gs = [state.g[i][k].view(torch.int16).cpu().numpy().view(np.uint16) for k in range(n_sets)]
+                t0 = time.perf_counter()
+                for step in range(1, args.warmup + args.steps + 1):
+                    ref.optimizer_step(rule, want[0], want[1], want[2], gs[(step - 1) % n_sets], want[3], step=step,
+                                       threads=0, **hp_kw)
+                t_or += time.perf_counter() - t0
+                for dev_t, host_a in ((state.p[i], want[0]), (state.m[i], want[1]), (state.v[i], want[2])):
+                    bad += int(np.count_nonzero(dev_t.cpu().numpy().view(np.uint32) != host_a.view(np.uint32)))
+                bad += int(np.count_nonzero(state.lp[i].view(torch.int16).cpu().numpy().view(np.uint16) != want[3]))
+            r["gpu_mismatches_vs_oracle"] = bad
+            r["oracle_params_per_s"] = state.total * (args.warmup + args.steps) / t_or
+        log(f"[rules] {rule}: {value/1e9:.1f} G params/s, kernel {launch_s*1e6:.1f} us/launch, "
+            f"{r['kernel_GBps']:.0f} GB/s at 20 B/param, mismatches {r.get('gpu_mismatches_vs_oracle')}")
+        out[rule] = r
+        del state
+        torch.cuda.empty_cache()
+    out["workload"] = "c2 shape (4 x 31,000,000 resident, 1% zero grads) under Adagrad and RMSProp"
+    return out
 
 
 def bench_ceilings(args, dos, torch, np):
@@ -570,7 +622,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--extra", default="c1,c3,c4", help="comma list of extra workloads (c1, c3, c4) or 'none'")
+    ap.add_argument("--extra", default="c1,c3,c4,rules",
+                    help="comma list of extra workloads (c1, c3, c4, rules = Adagrad and RMSProp on the c2 shape) "
+                         "or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
@@ -606,6 +660,8 @@ def main():
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
     if "c4" in wanted:
         extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
+    if "rules" in wanted:
+        extra["other_update_rules"] = bench_other_rules(args, dos, torch, np)
     if args.ceilings:
         extra["hbm_stream_ceilings"] = bench_ceilings(args, dos, torch, np)
     if args.ablation:

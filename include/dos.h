@@ -74,12 +74,28 @@ typedef struct dos_subgroup {
   int32_t grad_loc;  /* dos_loc of g                                      */
 } dos_subgroup;
 
-/* AdamW hyper-parameters as binary32 values; step is 1-based and names the step
- * being taken (it is not modified).  Valid: step >= 1, 0 <= beta < 1, eps >= 0,
- * all values finite. */
+/* Update rules.  Section 4.1 names Adam, Adagrad and RMSProp as the adaptive
+ * optimizers whose per-element independence the interleaving relies on.
+ *   DOS_OPT_ADAMW    bias-corrected Adam with decoupled weight decay; state p, m, v
+ *   DOS_OPT_ADAGRAD  v += g*g;                   p = p*(1-lr*wd) - lr*g/(sqrt(v)+eps)
+ *   DOS_OPT_RMSPROP  v = a*v + (1-a)*g*g (a = beta2, uncentred, no momentum);
+ *                                                p = p*(1-lr*wd) - lr*g/(sqrt(v)+eps)
+ * Adagrad and RMSProp keep p and v only: the m pointer of a subgroup is not
+ * read and may be NULL, the interleaved phase stages two FP32 arrays instead of
+ * three (8 bytes per parameter each way), and the resident update moves 20 bytes
+ * per parameter (reads 4+4+2, writes 4+4+2). */
+typedef enum dos_optimizer { DOS_OPT_ADAMW = 0, DOS_OPT_ADAGRAD = 1, DOS_OPT_RMSPROP = 2 } dos_optimizer;
+
+/* Hyper-parameters as binary32 values; step is 1-based and names the step
+ * being taken (it is not modified).  Valid: step >= 1, eps >= 0, all values
+ * finite, optimizer one of dos_optimizer; 0 <= beta < 1 for the betas the rule
+ * uses (AdamW both, RMSProp beta2 as its smoothing constant, Adagrad none).  A
+ * zero-initialised optimizer field means AdamW. */
 typedef struct dos_hparams {
   float lr, beta1, beta2, eps, weight_decay;
   int64_t step;
+  int32_t optimizer; /* dos_optimizer; last, so that initialisers written for the
+                        first six members keep meaning AdamW */
 } dos_hparams;
 
 /* Launch shape of the fused kernel, for tuning sweeps. */
@@ -93,7 +109,8 @@ typedef struct dos_launch_cfg {
 } dos_launch_cfg;
 
 /* ---- device-resident update (Algorithm 1, gpu_update) ---------------------
- * Fused AdamW over one subgroup whose five arrays are all device memory.
+ * Fused update (hp->optimizer; AdamW unless said otherwise) over one subgroup
+ * whose arrays are all device memory.
  * Asynchronous on hip_stream (a hipStream_t, NULL = the default stream); no
  * allocation, no synchronisation.  HBM traffic is 28 bytes per element (reads
  * 4+4+4+2, writes 4+4+4+2).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
@@ -107,10 +124,12 @@ dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hi
  * 4: one trip and no tile loop (block b owns tile b and nothing else; grid_blocks
  * must be 0); bit 4 (0x10) makes the loads non-temporal; bits 5-6 pick the store
  * policy: 0x20 non-temporal, 0x40 non-temporal at system scope without the
- * wave-level bit (sc1 nt), 0x60 non-temporal at system scope (sc0 sc1 nt).
+ * wave-level bit (sc1 nt), 0x60 non-temporal at system scope (sc0 sc1 nt); the two
+ * system-scope policies exist in layout 4 only.
  * dos_adam_step uses variant 0x74 with 64-thread blocks and an LDS request of
  * 14848 bytes per block (11 one-wave blocks per compute unit).  A NULL cfg means
- * those defaults; unknown values, lds_bytes above 65536: DOS_EINVAL. */
+ * those defaults; unknown values, lds_bytes above 65536: DOS_EINVAL.  Adagrad and
+ * RMSProp exist in layout 4 only (other layouts: DOS_EINVAL). */
 dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
                              const dos_launch_cfg* cfg);
 
@@ -131,6 +150,8 @@ typedef struct dos_cost_model {
   double gpu_params_per_s, cpu_params_per_s;
   double downscale_params_per_s;
   double launch_overhead_s;
+  int32_t fp32_arrays; /* FP32 state arrays staged per subgroup: 3 (p, m, v; also
+                          meant by 0) or 2 (p, v: Adagrad, RMSProp)               */
 } dos_cost_model;
 
 enum { DOS_PLAN_STRIDE = 0, DOS_PLAN_BALANCED = 1 };

@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libdos.so")
 DOS_OK, DOS_EINVAL, DOS_EALIGN, DOS_EBUDGET, DOS_EHIP, DOS_ESTATE = 0, -1, -2, -3, -4, -5
 DOS_HOST_PINNED, DOS_DEVICE, DOS_HOST_PAGEABLE = 0, 1, 2
 DOS_ON_CPU, DOS_ON_GPU = 0, 1
+DOS_OPT_ADAMW, DOS_OPT_ADAGRAD, DOS_OPT_RMSPROP = 0, 1, 2
 DOS_PLAN_STRIDE, DOS_PLAN_BALANCED = 0, 1
 DOS_CTX_PROFILE = 1
 DOS_CTX_UPLOAD_DMA = 2
@@ -27,7 +28,7 @@ class dos_subgroup(C.Structure):
 
 class dos_hparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("step", C.c_int64)]
+                ("weight_decay", C.c_float), ("step", C.c_int64), ("optimizer", C.c_int32)]
 
 
 class dos_launch_cfg(C.Structure):
@@ -38,7 +39,7 @@ class dos_launch_cfg(C.Structure):
 class dos_cost_model(C.Structure):
     _fields_ = [("h2d_Bps", C.c_double), ("d2h_Bps", C.c_double), ("gpu_params_per_s", C.c_double),
                 ("cpu_params_per_s", C.c_double), ("downscale_params_per_s", C.c_double),
-                ("launch_overhead_s", C.c_double)]
+                ("launch_overhead_s", C.c_double), ("fp32_arrays", C.c_int32)]
 
 
 class dos_plan(C.Structure):
@@ -147,8 +148,12 @@ def check(status: int, where: str) -> None:
 
 # ------------------------------------------------------------- marshalling helpers
 
-def hparams(lr, beta1, beta2, eps, weight_decay, step) -> dos_hparams:
-    return dos_hparams(lr, beta1, beta2, eps, weight_decay, int(step))
+OPTIMIZERS = {"adamw": DOS_OPT_ADAMW, "adagrad": DOS_OPT_ADAGRAD, "rmsprop": DOS_OPT_RMSPROP}
+
+
+def hparams(lr, beta1, beta2, eps, weight_decay, step, optimizer=DOS_OPT_ADAMW) -> dos_hparams:
+    """optimizer: a dos_optimizer value or one of "adamw", "adagrad", "rmsprop"."""
+    return dos_hparams(lr, beta1, beta2, eps, weight_decay, int(step), int(OPTIMIZERS.get(optimizer, optimizer)))
 
 
 def subgroup(p, m, v, g, p_lp, n, state_loc, grad_loc) -> dos_subgroup:
@@ -220,9 +225,9 @@ class Plan:
 
 
 def cost_model(h2d_Bps, d2h_Bps, gpu_params_per_s, cpu_params_per_s, downscale_params_per_s=0.0,
-               launch_overhead_s=0.0) -> dos_cost_model:
+               launch_overhead_s=0.0, fp32_arrays=3) -> dos_cost_model:
     return dos_cost_model(h2d_Bps, d2h_Bps, gpu_params_per_s, cpu_params_per_s,
-                          downscale_params_per_s, launch_overhead_s)
+                          downscale_params_per_s, launch_overhead_s, int(fp32_arrays))
 
 
 def dos_plan_subgroups(cm: dos_cost_model, sizes, gpu_budget_bytes: int, mode: int = DOS_PLAN_BALANCED,

@@ -19,29 +19,42 @@ namespace dos {
 dos_status make_scalars(const dos_hparams* hp, AdamScalars* out) {
   if (!hp || !out) return DOS_EINVAL;
   const float lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, eps = hp->eps, wd = hp->weight_decay;
+  const int opt = hp->optimizer;
+  if (opt != DOS_OPT_ADAMW && opt != DOS_OPT_ADAGRAD && opt != DOS_OPT_RMSPROP) return DOS_EINVAL;
   if (hp->step < 1) return DOS_EINVAL;
-  if (!isfinite(lr) || !isfinite(wd) || !isfinite(eps)) return DOS_EINVAL;
-  if (!(b1 >= 0.0f && b1 < 1.0f) || !(b2 >= 0.0f && b2 < 1.0f) || !(eps >= 0.0f)) return DOS_EINVAL;
-  const double t = (double)hp->step;
-  const double bc1 = 1.0 - pow((double)b1, t);
-  const double bc2 = 1.0 - pow((double)b2, t);
-  out->beta1 = b1;
-  out->beta2 = b2;
-  out->omb1 = 1.0f - b1;
-  out->omb2 = 1.0f - b2;
-  out->step_size = (float)((double)lr / bc1);
-  out->inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+  if (!isfinite(lr) || !isfinite(wd) || !isfinite(eps) || !(eps >= 0.0f)) return DOS_EINVAL;
+  if (opt == DOS_OPT_ADAMW && !(b1 >= 0.0f && b1 < 1.0f)) return DOS_EINVAL;
+  if (opt != DOS_OPT_ADAGRAD && !(b2 >= 0.0f && b2 < 1.0f)) return DOS_EINVAL;
+  memset(out, 0, sizeof *out);
+  out->opt = opt;
   out->eps = eps;
   out->decay = (float)(1.0 - (double)lr * (double)wd);
+  if (opt == DOS_OPT_ADAMW) {
+    const double t = (double)hp->step;
+    const double bc1 = 1.0 - pow((double)b1, t);
+    const double bc2 = 1.0 - pow((double)b2, t);
+    out->beta1 = b1;
+    out->beta2 = b2;
+    out->omb1 = 1.0f - b1;
+    out->omb2 = 1.0f - b2;
+    out->step_size = (float)((double)lr / bc1);
+    out->inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+  } else {
+    out->step_size = lr;  // no bias correction: the step index does not enter
+    if (opt == DOS_OPT_RMSPROP) {
+      out->beta2 = b2;
+      out->omb2 = 1.0f - b2;
+    }
+  }
   return DOS_OK;
 }
 
-dos_status check_subgroup_pointers(const dos_subgroup* sg) {
+dos_status check_subgroup_pointers(const dos_subgroup* sg, bool needs_m) {
   if (!sg) return DOS_EINVAL;
   if (sg->n == 0) return DOS_OK;
-  if (!sg->p || !sg->m || !sg->v || !sg->g || !sg->p_lp) return DOS_EINVAL;
-  const uintptr_t bits = (uintptr_t)sg->p | (uintptr_t)sg->m | (uintptr_t)sg->v | (uintptr_t)sg->g |
-                         (uintptr_t)sg->p_lp;
+  if (!sg->p || (needs_m && !sg->m) || !sg->v || !sg->g || !sg->p_lp) return DOS_EINVAL;
+  const uintptr_t bits = (uintptr_t)sg->p | (needs_m ? (uintptr_t)sg->m : 0) | (uintptr_t)sg->v |
+                         (uintptr_t)sg->g | (uintptr_t)sg->p_lp;
   if (bits & 15u) return DOS_EALIGN;
   return DOS_OK;
 }
@@ -81,20 +94,54 @@ void adam_block(float* __restrict__ p, float* __restrict__ m, float* __restrict_
   }
 }
 
+// Adagrad (RMS = false: v += g*g) and RMSProp (RMS = true: v = a*v + (1-a)*g*g) over
+// p and v; same operation order as the device kernel.
+template <bool RMS>
+inline void accum_body(float* __restrict__ p, float* __restrict__ v, const uint16_t* __restrict__ g,
+                       uint16_t* __restrict__ p_lp, uint64_t n, const AdamScalars s) {
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint32_t gb = (uint32_t)g[i] << 16;
+    float gi;
+    memcpy(&gi, &gb, 4);
+    const float vt = RMS ? s.beta2 * v[i] + (s.omb2 * gi) * gi : v[i] + gi * gi;
+    const float d = sqrtf(vt) + s.eps;
+    const float pt = p[i] * s.decay - s.step_size * (gi / d);
+    v[i] = vt;
+    p[i] = pt;
+    p_lp[i] = bf16_rne_host(pt);
+  }
+}
+#ifndef DOS_NO_TARGET_CLONES
+__attribute__((target_clones("avx512f", "avx2", "default")))
+#endif
+void adagrad_block(float* __restrict__ p, float* __restrict__ v, const uint16_t* __restrict__ g,
+                   uint16_t* __restrict__ p_lp, uint64_t n, const AdamScalars s) {
+  accum_body<false>(p, v, g, p_lp, n, s);
+}
+#ifndef DOS_NO_TARGET_CLONES
+__attribute__((target_clones("avx512f", "avx2", "default")))
+#endif
+void rmsprop_block(float* __restrict__ p, float* __restrict__ v, const uint16_t* __restrict__ g,
+                   uint16_t* __restrict__ p_lp, uint64_t n, const AdamScalars s) {
+  accum_body<true>(p, v, g, p_lp, n, s);
+}
+
 }  // namespace
 
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                      const AdamScalars& s) {
-  adam_block(p, m, v, g, p_lp, n, s);
+  if (s.opt == DOS_OPT_ADAGRAD) adagrad_block(p, v, g, p_lp, n, s);
+  else if (s.opt == DOS_OPT_RMSPROP) rmsprop_block(p, v, g, p_lp, n, s);
+  else adam_block(p, m, v, g, p_lp, n, s);
 }
 
 }  // namespace dos
 
 extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hparams* hp, int32_t threads) {
   dos::AdamScalars s;
-  dos_status rc = dos::check_subgroup_pointers(sg);
+  dos_status rc = dos::make_scalars(hp, &s);
   if (rc != DOS_OK) return rc;
-  rc = dos::make_scalars(hp, &s);
+  rc = dos::check_subgroup_pointers(sg, s.opt == DOS_OPT_ADAMW);
   if (rc != DOS_OK) return rc;
   if (sg->n == 0) return DOS_OK;
   if (sg->state_loc == DOS_DEVICE || sg->grad_loc == DOS_DEVICE) return DOS_ESTATE;
@@ -109,6 +156,7 @@ extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hpara
     dos::host_adam_range(sg->p, sg->m, sg->v, sg->g, sg->p_lp, n, s);
     return DOS_OK;
   }
+  float* const m = sg->m;  // NULL for the rules without a first moment: never offset
   // static split on 64-element boundaries
   const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
   std::vector<std::thread> pool;
@@ -118,7 +166,7 @@ extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hpara
     if (lo >= n) break;
     const uint64_t cnt = (lo + per <= n) ? per : n - lo;
     pool.emplace_back([=]() {
-      dos::host_adam_range(sg->p + lo, sg->m + lo, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
+      dos::host_adam_range(sg->p + lo, m ? m + lo : nullptr, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
     });
   }
   for (auto& th : pool) th.join();

@@ -27,6 +27,10 @@ namespace {
 // with 32, 6.45 with 9, 4.1 with 5 -- fewer waves keep fewer DRAM pages open at
 // once, too few no longer cover the latency.
 constexpr int64_t kDefaultLdsThrottle = 14848;
+// The two-array rules (Adagrad, RMSProp) move 20 instead of 28 bytes per element, so a
+// wave holds less traffic and the best cap is higher: 15 waves per CU (6.7 TB/s; 6.6 with
+// 11 or 17 waves).
+constexpr int64_t kDefaultLdsThrottleTwoArrays = 10923;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -37,34 +41,50 @@ __device__ __forceinline__ T ld(const T* ptr) {
   if constexpr (NT) return __builtin_nontemporal_load(ptr);
   else return *ptr;
 }
+// Stores of the layouts that address memory through plain pointers: plain or
+// non-temporal.
+template <int SP, typename T>
+__device__ __forceinline__ void st(T* ptr, T val) {
+  static_assert(SP == 0 || SP == 1, "system-scope store policies exist in the untiled layout only");
+  if constexpr (SP == 1) __builtin_nontemporal_store(val, ptr);
+  else *ptr = val;
+}
+
+// The untiled layout addresses its tile through buffer descriptors: the cache
+// policy of every access is an operand of the compiler's buffer builtins (bit 0
+// sc0, bit 1 nt, bit 4 sc1 on gfx950), so the compiler, not hand-written
+// instructions, keeps the wait states and counters right; and the descriptor's
+// size makes the hardware drop accesses past the last whole quad, so the ragged
+// last tile needs no branch (loads return 0, stores are discarded).
+template <bool NTL>
+constexpr int load_aux() { return NTL ? 2 : 0; }
 // Store policies: 0 plain, 1 non-temporal, 2 non-temporal at system scope without
-// the wave-level bit (sc1 nt), 3 non-temporal at system scope (sc0 sc1 nt).  The last
-// two are spelled out as instructions because no builtin produces them; the
-// scope bits only select the cache policy of a store (write-through towards
-// memory), the data path is the ordinary vector store.  The s_nop keeps one
-// wait state between a store of more than 8 bytes and a vector instruction that
-// overwrites its data registers, which the compiler cannot see to for an
-// instruction it does not parse.
+// the wave-level bit (sc1 nt), 3 non-temporal at system scope (sc0 sc1 nt).
 template <int SP>
-__device__ __forceinline__ void st(f32x4* ptr, f32x4 val) {
-  if constexpr (SP == 0) *ptr = val;
-  else if constexpr (SP == 1) __builtin_nontemporal_store(val, ptr);
-  else if constexpr (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
-  else asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
+constexpr int store_aux() { return SP == 0 ? 0 : SP == 1 ? 2 : SP == 2 ? 18 : 19; }
+
+// Descriptor over `bytes` bytes starting at `base` (wave-uniform): raw buffer, no
+// stride, 32-bit data format.  A tile is a few KiB, so clamping the size of what
+// is left of an array to 32 bits never cuts into the tile.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, uint64_t bytes) {
+  const uint32_t rec = bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)rec, 0x00020000);
+}
+template <bool NTL>
+__device__ __forceinline__ f32x4 buf_ld4(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, load_aux<NTL>()));
+}
+template <bool NTL>
+__device__ __forceinline__ u32x2 buf_ld2(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, load_aux<NTL>());
 }
 template <int SP>
-__device__ __forceinline__ void st(u32x2* ptr, u32x2 val) {
-  if constexpr (SP == 0) *ptr = val;
-  else if constexpr (SP == 1) __builtin_nontemporal_store(val, ptr);
-  else if constexpr (SP == 2) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
-  else asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
+__device__ __forceinline__ void buf_st4(__amdgpu_buffer_rsrc_t r, uint32_t off, f32x4 val) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), r, (int)off, 0, store_aux<SP>());
 }
 template <int SP>
-__device__ __forceinline__ void st(u32x4* ptr, u32x4 val) {
-  if constexpr (SP == 0) *ptr = val;
-  else if constexpr (SP == 1) __builtin_nontemporal_store(val, ptr);
-  else if constexpr (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
-  else asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 0" ::"v"(ptr), "v"(val) : "memory");
+__device__ __forceinline__ void buf_st2(__amdgpu_buffer_rsrc_t r, uint32_t off, u32x2 val) {
+  __builtin_amdgcn_raw_buffer_store_b64(val, r, (int)off, 0, store_aux<SP>());
 }
 
 // binary32 -> bf16 bit pattern, round to nearest even; NaN kept as quiet NaN.
@@ -86,6 +106,36 @@ __device__ __forceinline__ uint32_t adam_element(const AdamScalars& s, float& p,
   v = vt;
   p = pt;
   return bf16_rne(pt);
+}
+
+// Adagrad (RMS = false: v += g*g) and RMSProp (RMS = true: v = a*v + (1-a)*g*g): one
+// element of p and its accumulator v, no first moment; returns the bf16 bits of the
+// new parameter.
+template <bool RMS>
+__device__ __forceinline__ uint32_t accum_element(const AdamScalars& s, float& p, float& v, uint32_t g_bits_hi) {
+  const float g = __uint_as_float(g_bits_hi);
+  const float vt = RMS ? s.beta2 * v + (s.omb2 * g) * g : v + g * g;
+  const float d = __builtin_sqrtf(vt) + s.eps;
+  const float pt = p * s.decay - s.step_size * (g / d);
+  v = vt;
+  p = pt;
+  return bf16_rne(pt);
+}
+
+template <bool RMS>
+__device__ __forceinline__ u32x2 accum_quad(const AdamScalars& s, f32x4& p, f32x4& v, u32x2 g) {
+  float p0 = p.x, p1 = p.y, p2 = p.z, p3 = p.w;
+  float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
+  const uint32_t b0 = accum_element<RMS>(s, p0, v0, g.x << 16);
+  const uint32_t b1 = accum_element<RMS>(s, p1, v1, g.x & 0xFFFF0000u);
+  const uint32_t b2 = accum_element<RMS>(s, p2, v2, g.y << 16);
+  const uint32_t b3 = accum_element<RMS>(s, p3, v3, g.y & 0xFFFF0000u);
+  p.x = p0; p.y = p1; p.z = p2; p.w = p3;
+  v.x = v0; v.y = v1; v.z = v2; v.w = v3;
+  u32x2 out;
+  out.x = b0 | (b1 << 16);
+  out.y = b2 | (b3 << 16);
+  return out;
 }
 
 // Four consecutive elements held by one lane.
@@ -167,29 +217,58 @@ __global__ __launch_bounds__(512) void adam_kernel_quads(float* __restrict__ p, 
 }
 
 // Layout A without the tile loop: block b owns quads [b*blockDim, (b+1)*blockDim),
-// nothing else.  The shortest possible wave: address arithmetic, four loads, the
+// nothing else.  The shortest possible wave: five descriptors, four loads, the
 // update, four stores.
 template <bool NTL, int NTS>
 __global__ __launch_bounds__(512) void adam_kernel_tile(float* __restrict__ p, float* __restrict__ m,
                                                         float* __restrict__ v, const uint16_t* __restrict__ g,
                                                         uint16_t* __restrict__ p_lp, uint64_t n, AdamScalars s) {
-  const uint64_t n_quads = n >> 2;
-  const uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (q < n_quads) {
-    f32x4* p4 = reinterpret_cast<f32x4*>(p) + q;
-    f32x4* m4 = reinterpret_cast<f32x4*>(m) + q;
-    f32x4* v4 = reinterpret_cast<f32x4*>(v) + q;
-    const u32x2 G = ld<NTL>(reinterpret_cast<const u32x2*>(g) + q);
-    f32x4 P = ld<NTL>(p4);
-    f32x4 M = ld<NTL>(m4);
-    f32x4 V = ld<NTL>(v4);
-    const u32x2 o = adam_quad(s, P, M, V, G);
-    st<NTS>(m4, M);
-    st<NTS>(v4, V);
-    st<NTS>(p4, P);
-    st<NTS>(reinterpret_cast<u32x2*>(p_lp) + q, o);
+  const uint64_t whole = (n >> 2) << 2;                                // elements in whole quads
+  const uint64_t e0 = (uint64_t)blockIdx.x * blockDim.x * 4;           // first element of this tile
+  const uint64_t left = whole > e0 ? whole - e0 : 0;                   // whole-quad elements from e0 on
+  const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rm = tile_rsrc(m + e0, left * 4),
+                               rv = tile_rsrc(v + e0, left * 4), rg = tile_rsrc(g + e0, left * 2),
+                               ro = tile_rsrc(p_lp + e0, left * 2);
+  const uint32_t off4 = threadIdx.x * 16, off2 = threadIdx.x * 8;
+  const u32x2 G = buf_ld2<NTL>(rg, off2);
+  f32x4 P = buf_ld4<NTL>(rp, off4);
+  f32x4 M = buf_ld4<NTL>(rm, off4);
+  f32x4 V = buf_ld4<NTL>(rv, off4);
+  const u32x2 o = adam_quad(s, P, M, V, G);
+  buf_st4<NTS>(rm, off4, M);
+  buf_st4<NTS>(rv, off4, V);
+  buf_st4<NTS>(rp, off4, P);
+  buf_st2<NTS>(ro, off2, o);
+  adam_tail(p, m, v, g, p_lp, n >> 2, n, s);
+}
+
+// The same launch for the rules that keep p and one accumulator (Adagrad, RMSProp):
+// 20 bytes per element (reads 4+4+2, writes 4+4+2), the m array is never touched.
+template <bool RMS, bool NTL, int NTS>
+__global__ __launch_bounds__(512) void accum_kernel_tile(float* __restrict__ p, float* __restrict__ v,
+                                                         const uint16_t* __restrict__ g,
+                                                         uint16_t* __restrict__ p_lp, uint64_t n, AdamScalars s) {
+  const uint64_t whole = (n >> 2) << 2;
+  const uint64_t e0 = (uint64_t)blockIdx.x * blockDim.x * 4;
+  const uint64_t left = whole > e0 ? whole - e0 : 0;
+  const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rv = tile_rsrc(v + e0, left * 4),
+                               rg = tile_rsrc(g + e0, left * 2), ro = tile_rsrc(p_lp + e0, left * 2);
+  const uint32_t off4 = threadIdx.x * 16, off2 = threadIdx.x * 8;
+  const u32x2 G = buf_ld2<NTL>(rg, off2);
+  f32x4 P = buf_ld4<NTL>(rp, off4);
+  f32x4 V = buf_ld4<NTL>(rv, off4);
+  const u32x2 o = accum_quad<RMS>(s, P, V, G);
+  buf_st4<NTS>(rv, off4, V);
+  buf_st4<NTS>(rp, off4, P);
+  buf_st2<NTS>(ro, off2, o);
+  // elements [whole, n): at most three, handled by the first lanes of block 0
+  const uint64_t i = whole + threadIdx.x;
+  if (blockIdx.x == 0 && i < n) {
+    float pi = p[i], vi = v[i];
+    const uint32_t b = accum_element<RMS>(s, pi, vi, (uint32_t)g[i] << 16);
+    p[i] = pi; v[i] = vi;
+    p_lp[i] = (uint16_t)b;
   }
-  adam_tail(p, m, v, g, p_lp, n_quads, n, s);
 }
 
 // Layout B: a lane handles 8 consecutive elements per trip (two adjacent 16-byte
@@ -266,25 +345,24 @@ template <int MODE>
 __global__ __launch_bounds__(64) void probe_traffic_kernel(float* __restrict__ p, float* __restrict__ m,
                                                            float* __restrict__ v, const uint16_t* __restrict__ g,
                                                            uint16_t* __restrict__ p_lp, uint64_t n) {
-  const uint64_t n_quads = n >> 2;
-  const uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= n_quads) return;
-  f32x4* p4 = reinterpret_cast<f32x4*>(p) + q;
-  f32x4* m4 = reinterpret_cast<f32x4*>(m) + q;
-  f32x4* v4 = reinterpret_cast<f32x4*>(v) + q;
-  const u32x2* g4 = reinterpret_cast<const u32x2*>(g) + q;
-  u32x2* o4 = reinterpret_cast<u32x2*>(p_lp) + q;
+  const uint64_t whole = (n >> 2) << 2;
+  const uint64_t e0 = (uint64_t)blockIdx.x * blockDim.x * 4;
+  const uint64_t left = whole > e0 ? whole - e0 : 0;
+  const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rm = tile_rsrc(m + e0, left * 4),
+                               rv = tile_rsrc(v + e0, left * 4), rg = tile_rsrc(g + e0, left * 2),
+                               ro = tile_rsrc(p_lp + e0, left * 2);
+  const uint32_t off4 = threadIdx.x * 16, off2 = threadIdx.x * 8;
   f32x4 P = {0.f, 0.f, 0.f, 0.f}, M = P, V = P;
   u32x2 G = {0u, 0u};
   if (MODE != 1) {
-    G = __builtin_nontemporal_load(g4);
-    P = __builtin_nontemporal_load(p4);
-    M = __builtin_nontemporal_load(m4);
-    V = __builtin_nontemporal_load(v4);
+    G = buf_ld2<true>(rg, off2);
+    P = buf_ld4<true>(rp, off4);
+    M = buf_ld4<true>(rm, off4);
+    V = buf_ld4<true>(rv, off4);
   }
   if (MODE == 0) {
     // never true for the finite data the probe runs on; keeps the loads alive
-    if (P.x != P.x && M.y != M.y && V.z != V.z && G.x == 0x7FC17FC1u) *o4 = G;
+    if (P.x != P.x && M.y != M.y && V.z != V.z && G.x == 0x7FC17FC1u) buf_st2<3>(ro, off2, G);
     return;
   }
   if (MODE == 2) {
@@ -296,15 +374,28 @@ __global__ __launch_bounds__(64) void probe_traffic_kernel(float* __restrict__ p
     G.x ^= 0x00010001u;
     G.y ^= 0x00010001u;
   }
-  st<3>(m4, M);
-  st<3>(v4, V);
-  st<3>(p4, P);
-  st<3>(o4, G);
+  buf_st4<3>(rm, off4, M);
+  buf_st4<3>(rv, off4, V);
+  buf_st4<3>(rp, off4, P);
+  buf_st2<3>(ro, off2, G);
 }
 
 template <bool NTL, int NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStream_t st_, float* p, float* m, float* v,
                          const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s) {
+  if (s.opt != DOS_OPT_ADAMW) {  // the accumulator rules exist in the untiled layout only
+    if (layout != 4) return DOS_EINVAL;
+    if (s.opt == DOS_OPT_RMSPROP)
+      hipLaunchKernelGGL((accum_kernel_tile<true, NTL, NTS>), grid, block, lds, st_, p, v, g, lp, n, s);
+    else
+      hipLaunchKernelGGL((accum_kernel_tile<false, NTL, NTS>), grid, block, lds, st_, p, v, g, lp, n, s);
+    return DOS_OK;
+  }
+  if constexpr (NTS >= 2) {  // system-scope stores exist in the untiled layout only
+    if (layout != 4) return DOS_EINVAL;
+    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s);
+    return DOS_OK;
+  } else {
   switch (layout) {
     case 0: hipLaunchKernelGGL((adam_kernel_quads<2, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
     case 1: hipLaunchKernelGGL((adam_kernel_quads<1, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
@@ -314,6 +405,7 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStrea
     default: return DOS_EINVAL;
   }
   return DOS_OK;
+  }
 }
 
 }  // namespace
@@ -330,7 +422,9 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   int threads = (cfg && cfg->block_threads) ? cfg->block_threads : 64;
   int64_t blocks = cfg ? cfg->grid_blocks : 0;
   // The kernel uses no LDS; a dynamic allocation only caps how many waves a CU holds.
-  int64_t lds = (cfg && cfg->lds_bytes) ? cfg->lds_bytes : kDefaultLdsThrottle;
+  int64_t lds = (cfg && cfg->lds_bytes) ? cfg->lds_bytes
+                : s.opt == DOS_OPT_ADAMW     ? kDefaultLdsThrottle
+                                             : kDefaultLdsThrottleTwoArrays;
   if (lds < 0) lds = 0;
   if (lds > 65536) return DOS_EINVAL;
   if (variant < 0 || threads < 64 || threads > 512 || (threads % 64) != 0 || blocks < 0) return DOS_EINVAL;

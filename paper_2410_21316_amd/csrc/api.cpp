@@ -25,9 +25,9 @@ extern "C" {
 dos_status dos_adam_step_cfg(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream,
                              const dos_launch_cfg* cfg) {
   dos::AdamScalars s;
-  dos_status rc = dos::check_subgroup_pointers(sg);
+  dos_status rc = dos::make_scalars(hp, &s);
   if (rc != DOS_OK) return rc;
-  rc = dos::make_scalars(hp, &s);
+  rc = dos::check_subgroup_pointers(sg, s.opt == DOS_OPT_ADAMW);
   if (rc != DOS_OK) return rc;
   if (sg->n == 0) return DOS_OK;
   if (sg->state_loc != DOS_DEVICE || sg->grad_loc != DOS_DEVICE) return DOS_ESTATE;

@@ -7,17 +7,24 @@
 
 namespace dos {
 
-// The eight binary32 scalars of one step, derived once on the host
-// (formed in double, each rounded to binary32 once).
+// The binary32 scalars of one step, derived once on the host (formed in double,
+// each rounded to binary32 once), and the update rule they belong to.  Adagrad
+// and RMSProp use beta2 / omb2 (RMSProp's smoothing constant), step_size (the
+// learning rate itself: no bias correction), eps and decay.
 struct AdamScalars {
   float beta1, beta2, omb1, omb2, step_size, inv_sqrt_bc2, eps, decay;
+  int32_t opt;  // dos_optimizer
 };
+
+// FP32 state arrays the rule keeps per subgroup: p, m, v or p, v.
+inline int fp32_arrays_of(int opt) { return opt == DOS_OPT_ADAMW ? 3 : 2; }
 
 // Validates the hyper-parameters and derives the scalars.
 dos_status make_scalars(const dos_hparams* hp, AdamScalars* out);
 
-// True when every pointer of the subgroup is non-NULL (or n == 0) and 16-byte aligned.
-dos_status check_subgroup_pointers(const dos_subgroup* sg);
+// DOS_OK when every pointer of the subgroup the rule uses is non-NULL (or n == 0)
+// and 16-byte aligned; m is only looked at when needs_m.
+dos_status check_subgroup_pointers(const dos_subgroup* sg, bool needs_m = true);
 
 // Enqueues the fused kernel over n elements on `stream`.  Pointers are device
 // memory, 16-byte aligned (checked by the callers).  Returns DOS_EHIP when the

@@ -110,6 +110,7 @@ struct dos_ctx {
   uint64_t pf_generation = 0;       // bumped to start a prefetch job
   bool pf_busy = false;             // a prefetch job is running
   bool pf_prof = false;             // the job records profile events
+  bool pf_needs_m = true;           // the rule keeps a first moment: m is staged too
   const dos_subgroup* pf_sgs = nullptr;
   int64_t pf_enqueued = -1;         // last piece whose prefetch and ready event are enqueued
   int64_t fl_enqueued = -1;         // last piece whose flush and freed event are enqueued
@@ -199,8 +200,8 @@ void worker_main(dos_ctx* c, int tid) {
       }
       uint16_t* out = reinterpret_cast<uint16_t*>(c->stage + (uint64_t)r * c->chunk_params * 2);
       const auto tw1 = clk::now();
-      dos::host_adam_range(sg.p + ch.off, sg.m + ch.off, sg.v + ch.off, sg.g + ch.off, out, ch.cnt,
-                           c->job_scalars);
+      dos::host_adam_range(sg.p + ch.off, sg.m ? sg.m + ch.off : nullptr, sg.v + ch.off, sg.g + ch.off, out,
+                           ch.cnt, c->job_scalars);
       const auto tw2 = clk::now();
       {
         std::lock_guard<std::mutex> lk(c->upl_mu);
@@ -244,7 +245,7 @@ inline SlotPtrs slot_of(const dos_ctx* c, size_t j) {
 // of piece j - n_slots has landed: a host wait, so that no stream ever holds a long
 // chain of blocked commands.  The caller has made sure that flush is enqueued.
 hipError_t prefetch_piece(dos_ctx* c, const dos_subgroup* sgs, const Piece& pc, size_t j, bool prof,
-                          const char** what) {
+                          bool needs_m, const char** what) {
   const dos_subgroup& sg = sgs[pc.sg];
   const int s = (int)(j % (size_t)c->n_slots);
   const SlotPtrs sl = slot_of(c, j);
@@ -258,7 +259,8 @@ hipError_t prefetch_piece(dos_ctx* c, const dos_subgroup* sgs, const Piece& pc, 
   *what = "prefetch of p";
   if ((e = hipMemcpyAsync(sl.p, sg.p + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
   *what = "prefetch of m";
-  if ((e = hipMemcpyAsync(sl.m, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
+  if (needs_m && (e = hipMemcpyAsync(sl.m, sg.m + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess)
+    return e;
   *what = "prefetch of v";
   if ((e = hipMemcpyAsync(sl.v, sg.v + pc.off, fb, hipMemcpyHostToDevice, c->h2d)) != hipSuccess) return e;
   *what = "prefetch of g";
@@ -282,7 +284,7 @@ void prefetcher_main(dos_ctx* c) {
     }
     const std::vector<Piece>& pieces = c->pieces;
     const dos_subgroup* sgs = c->pf_sgs;
-    const bool prof = c->pf_prof;
+    const bool prof = c->pf_prof, needs_m = c->pf_needs_m;
     for (size_t j = 0; j < pieces.size(); ++j) {
       if (j >= (size_t)c->n_slots) {
         // the flush that frees this slot must have been enqueued before its event means anything
@@ -291,7 +293,7 @@ void prefetcher_main(dos_ctx* c) {
         if (c->pipe_abort) break;
       }
       const char* what = "";
-      const hipError_t e = prefetch_piece(c, sgs, pieces[j], j, prof, &what);
+      const hipError_t e = prefetch_piece(c, sgs, pieces[j], j, prof, needs_m, &what);
       std::lock_guard<std::mutex> lk(c->pipe_mu);
       if (e != hipSuccess) {
         c->pf_error = e;
@@ -478,10 +480,11 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
   }
   uint64_t params_gpu = 0, params_cpu = 0, params_res = 0;
   int n_gpu = 0, n_cpu = 0, n_res = 0;
+  const bool needs_m = sc.opt == DOS_OPT_ADAMW;  // Adagrad, RMSProp: p and v only
   for (int k = 0; k < n_sg; ++k) {
     const int i = plan->order[k];
     const dos_subgroup& sg = sgs[i];
-    if ((rc = dos::check_subgroup_pointers(&sg)) != DOS_OK) return rc;
+    if ((rc = dos::check_subgroup_pointers(&sg, needs_m)) != DOS_OK) return rc;
     if (plan->target[i] > DOS_ON_GPU) return DOS_EINVAL;
     if (sg.state_loc < DOS_HOST_PINNED || sg.state_loc > DOS_HOST_PAGEABLE) return DOS_EINVAL;
     if (sg.grad_loc < DOS_HOST_PINNED || sg.grad_loc > DOS_HOST_PAGEABLE) return DOS_EINVAL;
@@ -554,7 +557,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       HIP_TRY(c, hipStreamWaitEvent(c->d2h, c->done[s], 0), "hipStreamWaitEvent");
       if (pe) HIP_TRY(c, hipEventRecord(pe[4], c->d2h), "hipEventRecord");
       HIP_TRY(c, hipMemcpyAsync(sg.p + pc.off, sl.p, fb, hipMemcpyDeviceToHost, c->d2h), "flush of p");
-      HIP_TRY(c, hipMemcpyAsync(sg.m + pc.off, sl.m, fb, hipMemcpyDeviceToHost, c->d2h), "flush of m");
+      if (needs_m) HIP_TRY(c, hipMemcpyAsync(sg.m + pc.off, sl.m, fb, hipMemcpyDeviceToHost, c->d2h), "flush of m");
       HIP_TRY(c, hipMemcpyAsync(sg.v + pc.off, sl.v, fb, hipMemcpyDeviceToHost, c->d2h), "flush of v");
       if (pe) HIP_TRY(c, hipEventRecord(pe[5], c->d2h), "hipEventRecord");
       HIP_TRY(c, hipEventRecord(c->freed[s], c->d2h), "hipEventRecord");
@@ -573,6 +576,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
         std::lock_guard<std::mutex> lk(c->pipe_mu);
         c->pf_sgs = sgs;
         c->pf_prof = prof;
+        c->pf_needs_m = needs_m;
         c->pf_enqueued = c->fl_enqueued = -1;
         c->pipe_abort = false;
         c->pf_error = hipSuccess;
@@ -660,10 +664,11 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
   if (stats) {
     memset(stats, 0, sizeof *stats);
     stats->wall_s = secs(t_entry, t_exit);
-    stats->h2d_bytes = 12.0 * (double)params_gpu + 2.0 * (double)params_cpu;
+    const double state_bytes = 4.0 * dos::fp32_arrays_of(sc.opt);  // per parameter and direction
+    stats->h2d_bytes = state_bytes * (double)params_gpu + 2.0 * (double)params_cpu;
     for (const Piece& pc : pieces)
       if (sgs[pc.sg].grad_loc == DOS_HOST_PINNED) stats->h2d_bytes += 2.0 * (double)pc.cnt;
-    stats->d2h_bytes = 12.0 * (double)params_gpu;
+    stats->d2h_bytes = state_bytes * (double)params_gpu;
     stats->h2d_busy_s = stats->d2h_busy_s = stats->gpu_busy_s = stats->duplex_overlap_s = -1.0;
     stats->h2d_span_s = stats->d2h_span_s = -1.0;
     stats->cpu_lane_s = chunks.empty() ? 0.0 : secs(c->cpu_first, c->cpu_last);

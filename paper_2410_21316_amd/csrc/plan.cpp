@@ -23,8 +23,11 @@ struct Cost {
   double predicted, lower;
 };
 
+// Bytes of FP32 state per parameter that cross the link in each direction.
+double state_bytes_of(const dos_cost_model& cm) { return cm.fp32_arrays == 2 ? 8.0 : 12.0; }
+
 bool valid_cost_model(const dos_cost_model* cm) {
-  return cm && cm->h2d_Bps > 0 && cm->d2h_Bps > 0 && cm->gpu_params_per_s > 0 &&
+  return cm && (cm->fp32_arrays == 0 || cm->fp32_arrays == 2 || cm->fp32_arrays == 3) && cm->h2d_Bps > 0 && cm->d2h_Bps > 0 && cm->gpu_params_per_s > 0 &&
          cm->cpu_params_per_s > 0 && cm->downscale_params_per_s >= 0 && cm->launch_overhead_s >= 0 &&
          isfinite(cm->h2d_Bps) && isfinite(cm->d2h_Bps) && isfinite(cm->gpu_params_per_s) &&
          isfinite(cm->cpu_params_per_s) && isfinite(cm->downscale_params_per_s) &&
@@ -52,7 +55,8 @@ Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* ta
       ++cg;
     }
   }
-  const double h2d_bytes = 12.0 * NG + 2.0 * NC, d2h_bytes = 12.0 * NG;
+  const double sb = state_bytes_of(cm);
+  const double h2d_bytes = sb * NG + 2.0 * NC, d2h_bytes = sb * NG;
   const double t_h2d = h2d_bytes / cm.h2d_Bps, t_d2h = d2h_bytes / cm.d2h_Bps;
   const double t_cpu = NC / cm.cpu_params_per_s;
   const double t_gpu = (NG + NR) / cm.gpu_params_per_s + cm.launch_overhead_s * (cg + cr);
@@ -61,10 +65,10 @@ Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* ta
     lane = std::max(t_h2d, t_gpu);
   } else if (n_slots >= 2) {
     if (slot_params > 0 && first > (double)slot_params) first = (double)slot_params;  // pieces
-    const double lead = 12.0 * first / cm.h2d_Bps + first / cm.gpu_params_per_s + cm.launch_overhead_s;
+    const double lead = sb * first / cm.h2d_Bps + first / cm.gpu_params_per_s + cm.launch_overhead_s;
     lane = std::max(std::max(t_h2d, lead + t_d2h), t_gpu);
   } else {
-    lane = std::max(12.0 * NG / cm.h2d_Bps + t_gpu + t_d2h, t_h2d);
+    lane = std::max(sb * NG / cm.h2d_Bps + t_gpu + t_d2h, t_h2d);
   }
   return {std::max(t_cpu, lane), std::max(t_h2d, t_d2h)};
 }
@@ -120,7 +124,7 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   // (a resident's state lives on the device, so it does not matter whether its
   // host copy could be pinned: cpu_only does not exclude residency)
   for (int i = n_sg - 1; i >= 0 && n_res < n_resident_max; --i) {
-    const uint64_t need = 12 * sizes[i];
+    const uint64_t need = (uint64_t)state_bytes_of(*cm) * sizes[i];
     if (need > left) break;
     left -= need;
     resident[i] = 1;
@@ -139,7 +143,8 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
   double k_real = 0.0;
   int k = 0;
   if (den > 0.0) {
-    k_real = (3.0 / B + 1.0 / cm->gpu_params_per_s) / den;
+    // (the 3 of Eq. 1 is the number of FP32 arrays that cross the link each way)
+    k_real = (state_bytes_of(*cm) / 4.0 / B + 1.0 / cm->gpu_params_per_s) / den;
     k = std::max(1, (int)(k_real + 0.5));
   }
 

@@ -75,10 +75,11 @@ class DeviceSubgroup:
                 self.lp[sl].view(torch.int16).cpu().numpy().view(np.uint16))
 
 
-def oracle_step(state, g_bits, hp, step, threads=0):
-    """state = [p, m, v, lp] numpy arrays, updated in place by the oracle."""
-    ref.adamw_step(state[0], state[1], state[2], np.ascontiguousarray(g_bits), state[3], step=step,
-                   threads=threads, **hp)
+def oracle_step(state, g_bits, hp, step, threads=0, optimizer="adamw"):
+    """state = [p, m, v, lp] numpy arrays, updated in place by the oracle's rule
+    of that name (Adagrad and RMSProp leave m alone)."""
+    ref.optimizer_step(optimizer, state[0], state[1], state[2], np.ascontiguousarray(g_bits), state[3], step=step,
+                       threads=threads, **hp)
 
 
 class Pinned:
@@ -158,10 +159,10 @@ class OffloadedState:
                 self.host[i]["g"][:] = bits
         torch.cuda.synchronize()
 
-    def oracle_step(self, hp, step):
+    def oracle_step(self, hp, step, optimizer="adamw"):
         for i, n in enumerate(self.sizes):
             if n:
-                oracle_step(self.ref[i], self.gbits[i], hp, step)
+                oracle_step(self.ref[i], self.gbits[i], hp, step, optimizer=optimizer)
 
     def current(self, i):
         if self.resident[i]:

@@ -108,7 +108,8 @@ int main() {
     plan.order = order.data();
     plan.resident = resident.data();
     for (int64_t step = 1; step <= 3; ++step) {
-      dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, step};
+      // the rule rotates with the iteration: AdamW, Adagrad, RMSProp
+      dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, step, (int32_t)(it % 3)};
       dos_phase_stats st{};
       const dos_status rc = dos_run_update_phase(ctx, sgs.data(), n_sg, &plan, &hp, &st);
       if (rc != DOS_OK) {
@@ -118,6 +119,7 @@ int main() {
       uint64_t total = 0;
       for (auto s : sizes) total += s;
       if (st.params_gpu + st.params_cpu + st.params_resident != total) return fail("stats do not add up");
+      if (st.d2h_bytes != (it % 3 ? 8.0 : 12.0) * (double)st.params_gpu) return fail("flush bytes do not fit the rule");
       for (int i = 0; i < n_sg; ++i) {
         if (dos_adam_step_host(&ref[i], &hp, 1) != DOS_OK) return fail("dos_adam_step_host failed");
         const uint64_t n = sizes[i];

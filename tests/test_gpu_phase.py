@@ -20,7 +20,7 @@ SIZES = [300_001, 262_144, 100_000, 65, 0, 500_003, 1_000_000, 64, 131_073]
 
 def run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=3, resident=None,
                    grad_on_device=None, host_threads=4, chunk_params=1 << 16, ring_chunks=6, flags=0,
-                   seed=S.BASE_SEED, **gkw):
+                   seed=S.BASE_SEED, optimizer="adamw", **gkw):
     st = OffloadedState(sizes, seed, resident=resident, grad_on_device=grad_on_device, **gkw)
     ctx = make_context(n_slots, slot_params, host_threads, chunk_params, ring_chunks, flags=flags)
     plan = dos.Plan.manual(targets, order, n_slots, slot_params, resident)
@@ -28,9 +28,9 @@ def run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=3, res
     try:
         for step in range(1, steps + 1):
             st.set_grads(step)
-            stats = ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, **hp))
-            st.oracle_step(hp, step)
-            st.check(f"step {step} targets {targets} slots {n_slots}x{slot_params}")
+            stats = ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, optimizer=optimizer, **hp))
+            st.oracle_step(hp, step, optimizer=optimizer)
+            st.check(f"{optimizer} step {step} targets {targets} slots {n_slots}x{slot_params}")
     finally:
         ctx.close()
         st.free()
@@ -63,6 +63,23 @@ def test_random_plans_slots_pieces_and_orders(case, hp):
     run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=2, grad_on_device=grad_dev,
                    host_threads=rng.choice([1, 3, 8]), chunk_params=rng.choice([1 << 12, 1 << 16]),
                    ring_chunks=rng.choice([2, 3, 9]), seed=S.BASE_SEED + case, zero_pct=5.0, heavy_tail=True)
+
+
+@pytest.mark.parametrize("optimizer", ["adagrad", "rmsprop"])
+def test_other_rules_through_the_phase(optimizer, hp):
+    """Adagrad and RMSProp: mixed plan with a resident, device and host gradients, pieces smaller than
+    the subgroups; only p and v cross the link (8 bytes per parameter each way), m is left alone."""
+    n = len(SIZES)
+    targets = [1, 0, 1, 1, 0, 0, 1, 1, 1]
+    resident = [0, 0, 0, 0, 0, 0, 0, 0, 1]
+    grad_dev = [1, 0, 0, 1, 0, 0, 1, 0, 1]
+    stats = run_phase_case(SIZES, targets, list(reversed(range(n))), 3, 1 << 17, hp, resident=resident,
+                           grad_on_device=grad_dev, optimizer=optimizer, zero_pct=5.0, heavy_tail=True)
+    staged = sum(s for s, t, r in zip(SIZES, targets, resident) if t and not r)
+    on_cpu = sum(s for s, t in zip(SIZES, targets) if not t)
+    spilled = sum(s for s, t, r, gd in zip(SIZES, targets, resident, grad_dev) if t and not r and not gd)
+    assert stats.d2h_bytes == 8.0 * staged
+    assert stats.h2d_bytes == 8.0 * staged + 2.0 * on_cpu + 2.0 * spilled
 
 
 def test_all_gpu_and_all_cpu_plans(hp):

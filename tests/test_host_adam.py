@@ -41,6 +41,46 @@ def test_host_update_is_bit_identical_to_oracle(n, threads, hp):
             assert a.tobytes() == b.tobytes(), (name, step)
 
 
+@pytest.mark.parametrize("optimizer", ["adagrad", "rmsprop"])
+@pytest.mark.parametrize("n,threads", [(1, 1), (4097, 1), (300_001, 4)])
+def test_host_update_of_the_other_rules_is_bit_identical_to_oracle(optimizer, n, threads, hp):
+    """Adagrad and RMSProp on the host cores: p and v only, the first-moment pointer may be NULL."""
+    seed = S.BASE_SEED + n + 5
+    mine = make_state(n, seed)
+    theirs = [x.copy() for x in mine]
+    bf = lambda x: ref.f32_to_bf16(np.array(x, np.float32))
+    for step in range(1, 5):
+        set_grads(mine[3], seed, step, zero_pct=1.0, heavy_tail=True)
+        if n > 16:
+            mine[3][:8] = bf([1e-30, -1e-25, 3e38, -3e38, 0.0, -0.0, np.inf, np.nan])
+        theirs[3][:] = mine[3]
+        sg = dos.subgroup(mine[0].ctypes.data, None, mine[2].ctypes.data, mine[3].ctypes.data, mine[4].ctypes.data,
+                          n, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+        dos.dos_adam_step_host(sg, dos.hparams(step=step, optimizer=optimizer, **hp), threads)
+        ref.optimizer_step(optimizer, *theirs, step=step, threads=0, **hp)
+        for a, b, name in zip(mine, theirs, "p m v g p_lp".split()):
+            assert a.tobytes() == b.tobytes(), (optimizer, name, step)
+    assert not mine[1].any()
+
+
+def test_hyper_parameter_checks_follow_the_rule(hp):
+    import ctypes as C
+    lib = dos.load()
+    mine = make_state(64, S.BASE_SEED)
+    sg = dos.subgroup(*(a.ctypes.data for a in mine), 64, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+    call = lambda **kw: lib.dos_adam_step_host(C.byref(sg), C.byref(dos.hparams(**{**hp, "step": 1, **kw})), 1)
+    assert call(optimizer=3) == dos.DOS_EINVAL and call(optimizer=-1) == dos.DOS_EINVAL
+    # a beta the rule does not use is not looked at
+    assert call(optimizer="adagrad", beta1=7.0, beta2=-3.0) == dos.DOS_OK
+    assert call(optimizer="rmsprop", beta1=7.0) == dos.DOS_OK
+    assert call(optimizer="rmsprop", beta2=1.0) == dos.DOS_EINVAL
+    assert call(optimizer="adamw", beta1=1.0) == dos.DOS_EINVAL
+    for opt in ("adamw", "adagrad", "rmsprop"):
+        assert call(optimizer=opt, step=0) == dos.DOS_EINVAL
+        assert call(optimizer=opt, eps=-1.0) == dos.DOS_EINVAL
+        assert call(optimizer=opt, lr=float("inf")) == dos.DOS_EINVAL
+
+
 def test_host_update_heavy_tail_and_extreme_values(hp):
     """Heavy-tailed gradients with exact zeros, plus hand-placed extremes: values
     whose square underflows, huge gradients, denormal state, infinities, NaN."""

@@ -254,6 +254,38 @@ def test_cost_model_observe_takes_the_measured_rates():
     assert lib.dos_cost_model_observe(None, C.byref(st)) == dos.DOS_EINVAL
 
 
+def test_two_array_rules_move_eight_bytes_per_parameter():
+    """Adagrad and RMSProp keep p and v only (Section 4.1 names them next to Adam): the link terms of
+    the estimate and of Eq. 1 shrink from three FP32 arrays to two, and residents need 8 B/param."""
+    sizes = [100_000_000] * 20
+    tg = [i % 2 for i in range(20)]
+    cm3 = dos.cost_model(50e9, 40e9, 200e9, 4e9)
+    cm2 = dos.cost_model(50e9, 40e9, 200e9, 4e9, fp32_arrays=2)
+    assert dos.cost_model(50e9, 40e9, 200e9, 4e9, fp32_arrays=0).fp32_arrays == 0   # 0 means 3
+    p3, l3 = dos.dos_plan_cost(cm3, sizes, tg, 3, None, 16 << 20)
+    p2, l2 = dos.dos_plan_cost(cm2, sizes, tg, 3, None, 16 << 20)
+    p0, l0 = dos.dos_plan_cost(dos.cost_model(50e9, 40e9, 200e9, 4e9, fp32_arrays=0), sizes, tg, 3, None, 16 << 20)
+    assert (p0, l0) == (p3, l3)
+    ng = nc = 1e9
+    assert l3 == pytest.approx(max((12 * ng + 2 * nc) / 50e9, 12 * ng / 40e9))
+    assert l2 == pytest.approx(max((8 * ng + 2 * nc) / 50e9, 8 * ng / 40e9))
+    # Eq. 1 with two arrays: k = (2/B + 1/U_g) / (1/U_c - 1/(2B)), B in parameters per second
+    B = 50e9 / 4
+    plan = dos.dos_plan_subgroups(cm2, sizes, 4 * 10**9, dos.DOS_PLAN_STRIDE)
+    assert plan.c.stride_k_real == pytest.approx((2 / B + 1 / 200e9) / (1 / 4e9 - 1 / (2 * B)))
+    # cheaper staging moves more subgroups to the GPU
+    n3 = sum(dos.dos_plan_subgroups(cm3, sizes, 4 * 10**9).targets)
+    n2 = sum(dos.dos_plan_subgroups(cm2, sizes, 4 * 10**9).targets)
+    assert n2 > n3 > 0
+    # residents: 8 bytes per parameter of budget each
+    budget = 3 * 12 * (16 << 20) + 5 * 8 * 100_000_000
+    assert sum(dos.dos_plan_subgroups(cm2, sizes, budget, n_resident_max=20).residents) == 5
+    assert sum(dos.dos_plan_subgroups(cm3, sizes, budget, n_resident_max=20).residents) == 3
+    bad = dos.cost_model(50e9, 40e9, 200e9, 4e9, fp32_arrays=4)
+    with pytest.raises(dos.DosError):
+        dos.dos_plan_subgroups(bad, sizes, 4 * 10**9)
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_balanced_plan_invariants_on_random_machines(seed):
     """Whatever the rates: the balanced plan is never worse (by its own estimate)
