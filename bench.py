@@ -390,7 +390,7 @@ def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp=12, cpu
 
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
                     cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced",
-                    fresh_grads=True, spill_grads=False, pageable_rest=False):
+                    fresh_grads=True, spill_grads=False, pageable_rest=False, rule="adamw"):
     """Plan + run the interleaved phase on a host-offloaded state; returns a dict.
     fresh_grads=False generates the gradients once and reuses them for every step;
     spill_grads=True keeps every gradient in pinned host memory (GPU-planned subgroups fetch theirs
@@ -421,6 +421,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
                          stage_grads=spill_grads)
     if cm is None:
         cm = ctx.dos_calibrate()
+        cm.fp32_arrays = 3 if rule == "adamw" else 2    # Adagrad, RMSProp stage p and v only
         log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
             f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (ring-sized, optimistic)")
     link = (cm.h2d_Bps, cm.d2h_Bps)
@@ -444,7 +445,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         if fresh_grads or step == 1:
             state.fill_grads(step, **gkw)
         state.sync_host_grads()
-        st = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, **hp_kw))
+        st = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, optimizer=rule, **hp_kw))
         lb_plan = max(st.h2d_bytes / link[0], st.d2h_bytes / link[1])
         r = {"step": step, "wall_s": st.wall_s, "n_gpu": st.n_gpu, "n_cpu": st.n_cpu, "n_resident": st.n_resident,
              "gpu_fraction": (st.params_gpu + st.params_resident) / max(1, sum(sizes)),
@@ -463,7 +464,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         if check:
             for i in range(len(sizes)):
                 gs = state.g[i][idxs[i].to("cuda:0")].view(torch.int16).cpu().numpy().view(np.uint16)
-                ref.adamw_step(samp[i][0], samp[i][1], samp[i][2], gs, samp[i][3], step=step, threads=0, **hp_kw)
+                ref.optimizer_step(rule, samp[i][0], samp[i][1], samp[i][2], gs, samp[i][3], step=step, threads=0,
+                                   **hp_kw)
     mism = None
     if check:
         mism = 0
@@ -499,9 +501,11 @@ def bench_c4(args, dos, torch, np):
     import dos_synth as S
     sizes = [100_000_000] * 130
     out = run_interleaved(dos, torch, np, sizes, 40 * 10**9, steps=5, warmup=3, host_threads=args.host_threads,
-                          gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4", pageable_rest=True)
+                          gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4", pageable_rest=True, rule=args.rule)
     out["workload"] = ("c4: 13B params, fp32 p/m/v (156 GB) in host memory, 130 subgroups of 100,000,000, "
                        "40 GB GPU budget, balanced plan re-derived per iteration; bf16 grads ~N(0,1e-3); 5 steps")
+    if args.rule != "adamw":
+        out["workload"] += f"; update rule {args.rule}: only p and v are updated and staged (8 B/param each way)"
     if out["n_subgroups_pinned"] < out["n_subgroups"]:
         out["workload"] += (f"; hipHostMalloc pins only {out['n_subgroups_pinned']} subgroups on this machine, the "
                             "others are in pageable host memory and are planned CPU-only")
@@ -626,6 +630,8 @@ def main():
                     help="comma list of extra workloads (c1, c3, c4, rules = Adagrad and RMSProp on the c2 shape) "
                          "or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
+    ap.add_argument("--rule", default="adamw", choices=["adamw", "adagrad", "rmsprop"],
+                    help="update rule of the interleaved workload c4 (the primary workload is always AdamW)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
     ap.add_argument("--ceilings", action="store_true",
