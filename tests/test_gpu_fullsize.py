@@ -124,6 +124,63 @@ def test_interleaved_phase_on_100m_subgroups_sampled(heavy, hp):
         state.free()
 
 
+@pytest.mark.parametrize("rule", ["adagrad", "rmsprop"])
+def test_other_rules_on_100m_subgroups_sampled(rule, hp):
+    """Adagrad and RMSProp at the benchmark's subgroup size: six device-resident subgroups of
+    100,000,000 (default launch), then six host-offloaded ones through the planner and the phase with
+    two staged arrays per subgroup, 3 steps each; the oracle owns 1/16 of every subgroup."""
+    sizes = [100_000_000] * 5 + [37_000_003]
+    seed = S.BASE_SEED + 6
+    state = W.ResidentState(sizes, seed, DEV)
+    idxs = [torch.from_numpy(W.sample_index(n)).to(DEV) for n in sizes]
+    want = [[state.p[i][idxs[i]].cpu().numpy()] + [np.zeros(idxs[i].numel(), np.float32) for _ in range(2)] +
+            [np.zeros(idxs[i].numel(), np.uint16)] for i in range(len(sizes))]
+    stream = torch.cuda.current_stream().cuda_stream
+    for step in (1, 2, 3):
+        state.fill_grads(0, step, zero_pct=1.0)
+        for sg in state.descs[0]:
+            dos.dos_adam_step(sg, dos.hparams(step=step, optimizer=rule, **hp), stream)
+        torch.cuda.synchronize()
+        for i in range(len(sizes)):
+            ref.optimizer_step(rule, want[i][0], want[i][1], want[i][2], bits(state.g[i][0][idxs[i]]), want[i][3],
+                               step=step, threads=0, **hp)
+    for i in range(len(sizes)):
+        got = tuple(t[idxs[i]].cpu().numpy() for t in (state.p[i], state.m[i], state.v[i]))
+        assert_parity(f"{rule} resident subgroup {i}", got, want[i][:3], bits(state.lp[i][idxs[i]]), want[i][3])
+        assert np.all(state.v[i][-1000:].cpu().numpy() >= 0) and not state.m[i].any()
+    del state
+    torch.cuda.empty_cache()
+
+    off = W.OffloadedState(sizes, seed + 1, DEV)
+    assert not off.truncated
+    cm = dos.cost_model(56e9, 48e9, 200e9, 7e9, fp32_arrays=2)
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
+    assert 0 < sum(plan.targets) < len(sizes)
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, len(os.sched_getaffinity(0)))
+    hidx = [i.cpu() for i in idxs]
+    want = [[off.hp[i][hidx[i]].numpy().copy()] + [np.zeros(hidx[i].numel(), np.float32) for _ in range(2)] +
+            [np.zeros(hidx[i].numel(), np.uint16)] for i in range(len(sizes))]
+    try:
+        for step in (1, 2, 3):
+            off.place(plan.targets, plan.residents)
+            off.fill_grads(step, heavy_tail=True, zero_pct=5.0)
+            off.sync_host_grads()
+            st = ctx.dos_run_update_phase(off.sgs, plan, dos.hparams(step=step, optimizer=rule, **hp))
+            assert st.d2h_bytes == 8.0 * st.params_gpu and st.params_gpu + st.params_cpu == sum(sizes)
+            for i in range(len(sizes)):
+                ref.optimizer_step(rule, want[i][0], want[i][1], want[i][2], bits(off.g[i][idxs[i]]), want[i][3],
+                                   step=step, threads=0, **hp)
+        for i in range(len(sizes)):
+            got = tuple(t[hidx[i]].numpy() for t in (off.hp[i], off.hm[i], off.hv[i]))
+            assert_parity(f"{rule} phase subgroup {i} target {plan.targets[i]}", got, want[i][:3],
+                          bits(off.lp[i][idxs[i]]), want[i][3])
+            assert np.any(off.hv[i][-64:].numpy() > 0) and not off.hm[i].any()
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        off.free()
+
+
 def test_subgroup_larger_than_32_bit_indices(hp):
     """One device-resident subgroup of 2^31 + 4099 parameters: element indices do
     not fit 32 bits and byte offsets pass 2^33.  The oracle owns three windows:
