@@ -106,6 +106,9 @@ typedef struct dos_launch_cfg {
   int32_t lds_bytes;     /* dynamic LDS per block, used only to cap the number of
                             resident waves per CU (160 KiB / lds_bytes blocks);
                             0 = default, negative = none                           */
+  int32_t xcd_group;     /* 0 = block b owns tile b (blocks, and so tiles, go round
+                            the 8 XCDs one by one); a power of two k = each XCD takes k
+                            consecutive tiles at a time (layout 4, AdamW only)       */
 } dos_launch_cfg;
 
 /* ---- device-resident update (Algorithm 1, gpu_update) ---------------------

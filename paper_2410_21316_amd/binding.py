@@ -33,7 +33,7 @@ class dos_hparams(C.Structure):
 
 class dos_launch_cfg(C.Structure):
     _fields_ = [("variant", C.c_int32), ("block_threads", C.c_int32), ("grid_blocks", C.c_int32),
-                ("lds_bytes", C.c_int32)]
+                ("lds_bytes", C.c_int32), ("xcd_group", C.c_int32)]
 
 
 class dos_cost_model(C.Structure):
@@ -178,8 +178,8 @@ def dos_adam_step(sg: dos_subgroup, hp: dos_hparams, stream: int = 0) -> None:
     check(load().dos_adam_step(C.byref(sg), C.byref(hp), C.c_void_p(stream)), "dos_adam_step")
 
 
-def dos_adam_step_cfg(sg, hp, stream=0, variant=0, block_threads=0, grid_blocks=0, lds_bytes=0) -> None:
-    cfg = dos_launch_cfg(variant, block_threads, grid_blocks, lds_bytes)
+def dos_adam_step_cfg(sg, hp, stream=0, variant=0, block_threads=0, grid_blocks=0, lds_bytes=0, xcd_group=0) -> None:
+    cfg = dos_launch_cfg(variant, block_threads, grid_blocks, lds_bytes, xcd_group)
     check(load().dos_adam_step_cfg(C.byref(sg), C.byref(hp), C.c_void_p(stream), C.byref(cfg)),
           "dos_adam_step_cfg")
 

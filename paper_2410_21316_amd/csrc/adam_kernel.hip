@@ -222,9 +222,19 @@ __global__ __launch_bounds__(512) void adam_kernel_quads(float* __restrict__ p, 
 template <bool NTL, int NTS>
 __global__ __launch_bounds__(512) void adam_kernel_tile(float* __restrict__ p, float* __restrict__ m,
                                                         float* __restrict__ v, const uint16_t* __restrict__ g,
-                                                        uint16_t* __restrict__ p_lp, uint64_t n, AdamScalars s) {
+                                                        uint16_t* __restrict__ p_lp, uint64_t n, AdamScalars s,
+                                                        uint32_t xcd_shift) {
   const uint64_t whole = (n >> 2) << 2;                                // elements in whole quads
-  const uint64_t e0 = (uint64_t)blockIdx.x * blockDim.x * 4;           // first element of this tile
+  // Blocks are handed to the 8 XCDs round-robin.  Natural mapping (xcd_shift = 32 or more): block b
+  // owns tile b, so the XCDs interleave tile by tile.  Otherwise each XCD takes 2^xcd_shift
+  // consecutive tiles at a time: dispatch slot seq of XCD x owns tile ((seq >> k) * 8 + x) << k | low
+  // bits of seq (the grid is a multiple of 8 << k, tiles past the end are dropped by the range check).
+  uint64_t t = blockIdx.x;
+  if (xcd_shift < 32) {
+    const uint64_t x = t & 7, seq = t >> 3;
+    t = ((((seq >> xcd_shift) << 3) + x) << xcd_shift) | (seq & ((1ull << xcd_shift) - 1));
+  }
+  const uint64_t e0 = t * blockDim.x * 4;                              // first element of this tile
   const uint64_t left = whole > e0 ? whole - e0 : 0;                   // whole-quad elements from e0 on
   const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rm = tile_rsrc(m + e0, left * 4),
                                rv = tile_rsrc(v + e0, left * 4), rg = tile_rsrc(g + e0, left * 2),
@@ -382,7 +392,7 @@ __global__ __launch_bounds__(64) void probe_traffic_kernel(float* __restrict__ p
 
 template <bool NTL, int NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStream_t st_, float* p, float* m, float* v,
-                         const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s) {
+                         const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s, uint32_t xcd_shift) {
   if (s.opt != DOS_OPT_ADAMW) {  // the accumulator rules exist in the untiled layout only
     if (layout != 4) return DOS_EINVAL;
     if (s.opt == DOS_OPT_RMSPROP)
@@ -393,7 +403,7 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStrea
   }
   if constexpr (NTS >= 2) {  // system-scope stores exist in the untiled layout only
     if (layout != 4) return DOS_EINVAL;
-    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s);
+    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift);
     return DOS_OK;
   } else {
   switch (layout) {
@@ -401,7 +411,7 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStrea
     case 1: hipLaunchKernelGGL((adam_kernel_quads<1, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
     case 2: hipLaunchKernelGGL((adam_kernel_quads<4, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
     case 3: hipLaunchKernelGGL((adam_kernel_octets<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
-    case 4: hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
+    case 4: hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift); break;
     default: return DOS_EINVAL;
   }
   return DOS_OK;
@@ -440,10 +450,21 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   if (n_tiles == 0) n_tiles = 1;  // tail only
   if (blocks == 0 || (uint64_t)blocks > n_tiles) blocks = (int64_t)n_tiles;
   if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;  // grid-stride covers the rest
+  // XCD-grouped tile order (untiled AdamW layout only): the grid becomes a multiple of 8 << k
+  uint32_t xcd_shift = 32;
+  if (cfg && cfg->xcd_group) {
+    const int64_t grp = cfg->xcd_group;
+    if (layout != 4 || s.opt != DOS_OPT_ADAMW || grp < 1 || grp > (1 << 20) || (grp & (grp - 1))) return DOS_EINVAL;
+    xcd_shift = (uint32_t)__builtin_ctzll((unsigned long long)grp);
+    const int64_t unit = 8 * grp;
+    blocks = (blocks + unit - 1) / unit * unit;
+    if (blocks > 0x7FFFFFFF) return DOS_EINVAL;
+  }
   dim3 grid((unsigned)blocks), block((unsigned)threads);
   hipStream_t st_ = reinterpret_cast<hipStream_t>(stream);
   dos_status rc;
-#define DOS_LAUNCH(L, S) rc = launch_layout<L, S>(layout, grid, block, (size_t)lds, st_, p, m, v, g, p_lp, n, s)
+#define DOS_LAUNCH(L, S) \
+  rc = launch_layout<L, S>(layout, grid, block, (size_t)lds, st_, p, m, v, g, p_lp, n, s, xcd_shift)
   switch ((ntl ? 4 : 0) | sp) {
     case 0: DOS_LAUNCH(false, 0); break;
     case 1: DOS_LAUNCH(false, 1); break;

@@ -61,6 +61,14 @@ def test_untiled_layout_and_wave_cap_give_the_same_bits(variant, threads, lds, h
               zero_pct=5.0, heavy_tail=True)
 
 
+@pytest.mark.parametrize("n", [5, 300_007, (1 << 21) + 5])
+@pytest.mark.parametrize("group", [1, 2, 16, 1024, 1 << 20])
+def test_xcd_grouped_tile_order_gives_the_same_bits(n, group, hp):
+    """Each XCD taking `group` consecutive tiles at a time is only another order of the same tiles."""
+    run_steps(n, S.BASE_SEED + group, 2, hp, launch=dict(variant=0x74, xcd_group=group), zero_pct=5.0,
+              heavy_tail=True)
+
+
 # ---- Adagrad and RMSProp (Section 4.1 names them next to Adam): p and one accumulator
 
 @pytest.mark.parametrize("optimizer", ["adagrad", "rmsprop"])
@@ -171,6 +179,10 @@ def test_errors_leave_device_state_untouched(hp):
     cfg = dos.dos_launch_cfg(0x51, 64, 0)       # system-scope stores exist in the untiled layout only
     assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
     cfg = dos.dos_launch_cfg(4, 64, 8)          # the untiled layout takes no grid size
+    assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
+    cfg = dos.dos_launch_cfg(0x74, 64, 0, 0, 3)  # XCD groups are powers of two
+    assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
+    cfg = dos.dos_launch_cfg(1, 64, 0, 0, 4)     # and exist in the untiled layout only
     assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
     cfg = dos.dos_launch_cfg(1, 64, 0, 65537)   # more LDS than a block may request
     assert lib.dos_adam_step_cfg(C.byref(sg.desc), C.byref(good), None, C.byref(cfg)) == dos.DOS_EINVAL
