@@ -479,7 +479,20 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     timed = [r for r in results if r["timed"]]
     best = min(timed, key=lambda r: r["wall_s"])
     mean_wall = sum(r["wall_s"] for r in timed) / len(timed)
+    sb = 12.0 if rule == "adamw" else 8.0
+    res_params = sum(n for n, r in zip(sizes, plan.residents or [0] * len(sizes)) if r)
+    movable = [not c and not r for c, r in zip(state.cpu_only, plan.residents or [0] * len(sizes))]
+    lb_opt, k_opt = lower_bound_opt(sizes, movable, link, calibrated[2], calibrated[3], sb, res_params)
+    lb_free, k_free = lower_bound_opt(sizes, [not r for r in (plan.residents or [0] * len(sizes))], link,
+                                      calibrated[2], calibrated[3], sb, res_params)
     out = {"update_phase_s_per_iter": mean_wall, "best_s": best["wall_s"],
+           "lower_bound_opt_s": lb_opt, "lower_bound_opt_gpu_subgroups": k_opt,
+           "ratio_to_lower_bound_opt": mean_wall / lb_opt,
+           "lower_bound_opt_all_pinnable_s": lb_free, "ratio_to_lower_bound_opt_all_pinnable": mean_wall / lb_free,
+           "lower_bound_note": "ratio_to_lower_bound prices the executed plan's link bytes at the measured duplex "
+                               "link rates; lower_bound_opt is the best any split could reach with link, host "
+                               "update and GPU update all at their calibrated stand-alone peaks (over the "
+                               "subgroups this machine can pin; _all_pinnable: if it could pin all of them)",
            "params": sum(sizes), "n_subgroups": len(sizes), "n_subgroups_pinned": state.n_pinned,
            "params_per_s": sum(sizes) / mean_wall,
            "ratio_to_lower_bound": sum(r["ratio_to_lower_bound"] for r in timed) / len(timed),
@@ -495,6 +508,27 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     if own_state:
         state.free()
     return out
+
+
+def lower_bound_opt(sizes, movable, link, u_gpu, u_cpu, state_bytes, resident_params=0):
+    """The best any CPU/GPU split could do with every resource at its calibrated peak:
+    min over GPU sets of max(H2D time, D2H time, host update time, GPU update time).  Subgroups
+    are taken in decreasing size among the movable ones (those the link can reach); residents cost GPU
+    time only.  An all-GPU or all-CPU plan cannot game this bound the way it can a bound that prices
+    only the executed plan's link traffic."""
+    total = float(sum(sizes))
+    order = sorted((n for n, mv in zip(sizes, movable) if mv), reverse=True)
+    best = None
+    n_g = 0.0
+    for k in range(len(order) + 1):
+        if k:
+            n_g += order[k - 1]
+        n_c = total - n_g - resident_params
+        t = max((state_bytes * n_g + 2.0 * n_c) / link[0], state_bytes * n_g / link[1], n_c / u_cpu,
+                (n_g + resident_params) / u_gpu)
+        if best is None or t < best[0]:
+            best = (t, k)
+    return best
 
 
 def bench_c4(args, dos, torch, np):
