@@ -116,7 +116,7 @@ typedef struct dos_launch_cfg {
  * whose arrays are all device memory.
  * Asynchronous on hip_stream (a hipStream_t, NULL = the default stream); no
  * allocation, no synchronisation.  HBM traffic is 28 bytes per element (reads
- * 4+4+4+2, writes 4+4+4+2).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
+ * 4+4+4+2, writes 4+4+4+2; 20 bytes for the rules without a first moment).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
  * state_loc/grad_loc not DOS_DEVICE is DOS_ESTATE), DOS_EALIGN, DOS_EHIP. */
 dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);
 
@@ -177,7 +177,9 @@ typedef struct dos_plan {
 /* Pure, deterministic, host-only.
  *   mode DOS_PLAN_STRIDE:   k = (3/B + 1/U_g) / (1/U_c + 1/D_c - 1/(2B)) with B in
  *     parameters/s (h2d_Bps/4), rounded to nearest, at least 1; subgroup i goes
- *     to the GPU when (i+1) % k == 0 (Eq. 1 and Algorithm 1).
+ *     to the GPU when (i+1) % k == 0 (Eq. 1 and Algorithm 1).  The 3 is the
+ *     number of FP32 arrays that cross the link each way (cm->fp32_arrays: 2
+ *     for Adagrad and RMSProp).
  *   mode DOS_PLAN_BALANCED: minimises this library's own makespan estimate
  *     (dos_plan_cost) over the number and choice of GPU subgroups: exhaustively
  *     for up to 16 non-resident subgroups, otherwise an even spread of the best
@@ -216,8 +218,9 @@ enum {
   DOS_CTX_PROFILE = 1,    /* time every copy and kernel with events                            */
   DOS_CTX_UPLOAD_DMA = 2, /* send 16-bit uploads with hipMemcpyAsync instead of the default
                              pull-copy kernel (DMA uploads queue behind the bulk prefetches)  */
-  DOS_CTX_SPIN_WAIT = 4   /* the calling thread spins while it waits for a free slot instead
-                             of sleeping (takes a core from the host workers)                 */
+  DOS_CTX_SPIN_WAIT = 4   /* the two threads that drive the GPU lane spin while they wait for
+                             a slot or a piece instead of sleeping (takes cores from the host
+                             workers)                                                         */
 };
 
 typedef struct dos_ctx_config {
@@ -260,7 +263,8 @@ typedef struct dos_phase_stats {
                                      time a direction sat idle between its copies    */
 } dos_phase_stats;
 
-/* Creates a context: events, worker threads and (unless given) streams.  slot_mem
+/* Creates a context: events, worker threads, the prefetch thread of the GPU lane
+ * and (unless given) streams.  slot_mem
  * and pinned_stage stay owned by the caller and must outlive the context.  A
  * context runs one phase at a time; contexts that use the library's own streams
  * on the same device share them, so their phases should not overlap either.
@@ -269,17 +273,19 @@ typedef struct dos_phase_stats {
  * aligned), DOS_EBUDGET (slot_bytes < n_slots * 12 * slot_params, ring smaller
  * than two chunks), DOS_EHIP. */
 dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg);
-/* Joins the worker threads and releases the events; NULL is allowed. */
+/* Joins the context's threads and releases the events; NULL is allowed. */
 void dos_ctx_destroy(dos_ctx* ctx);
 
 /* One update phase over all subgroups (Algorithm 1 run_update, re-designed as
  * two concurrent lanes).  GPU-planned subgroups in pinned host memory are
- * prefetched into a staging slot (H2D stream), updated there (compute stream)
- * and flushed back (D2H stream), slot by slot, piece by piece; static residents
+ * prefetched into a staging slot (H2D stream, enqueued by the context's prefetch
+ * thread), updated there (compute stream) and flushed back (D2H stream, both
+ * enqueued by the calling thread), slot by slot, piece by piece; static residents
  * (state_loc == DOS_DEVICE) are updated in place, last; CPU-planned subgroups
  * (state and gradients in pinned or pageable host memory) are updated in place
  * by the host worker threads, which write the 16-bit parameters into the pinned
- * upload ring and send them to p_lp on the upload stream.
+ * upload ring and send them to p_lp on the upload stream.  hp->optimizer selects
+ * the rule for all of them; Adagrad and RMSProp stage and flush p and v only.
  * Synchronous at the boundary: on return every p, m, v is back where state_loc
  * says and every p_lp has landed on the device.  plan->target decides the lane
  * of each subgroup, plan->order the order in which each lane takes its subgroups
@@ -296,18 +302,23 @@ dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, c
 dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 
 /* Timeline of the GPU lane of the context's last phase (contexts created with
- * DOS_CTX_PROFILE, phases run with a non-NULL stats argument): for each staged piece, in the order they were processed, six
- * times in milliseconds since the phase's first command -- prefetch start and
- * end, kernel start and end, flush start and end.  Writes at most max_pieces
+ * DOS_CTX_PROFILE, phases run with a non-NULL stats argument): for each staged
+ * piece, in the order they were processed, six times in milliseconds since the
+ * phase's first command -- prefetch start and end, kernel start and end, flush
+ * start and end.  Writes at most max_pieces
  * rows of six floats into ms6 (a host buffer) and the number of pieces the phase
  * had into *n_pieces (0 when nothing was timed). */
 dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pieces, int32_t* n_pieces);
 
 /* Replaces the host-update rate and the link rates of `cm` by what the phase that
- * produced `st` actually reached (host lane: parameters / lane time; link: bytes /
- * summed copy time when the context profiles, else bytes / lane time as an upper
- * bound on the time).  Call it after every phase and re-plan: the plan then
- * tracks contention between the two lanes. */
+ * produced `st` actually reached.  Host lane: parameters / lane time.  Link, when
+ * the context profiles: bytes / summed copy time per direction, where the
+ * host-to-device direction also counts the 16-bit upload bytes that moved while
+ * prefetches were busy (the model charges them to that direction), and both
+ * rates are then lowered by a common factor until the model reproduces the
+ * measured GPU-lane time; without profiling: bytes / lane time as an upper bound
+ * on the time (rates only drop).  Call it after every phase and re-plan: the
+ * plan then tracks contention between the two lanes. */
 dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st);
 
 /* ---- utilities ------------------------------------------------------------ */
