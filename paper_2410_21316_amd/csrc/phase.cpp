@@ -420,7 +420,8 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     if ((e = hipEventCreateWithFlags(&c->ready[s], hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
       return fail(e, "hipEventCreate");
     if ((e = hipEventCreateWithFlags(&c->done[s], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
-    // the driver thread sleeps on this one (it must not take a core from the workers)
+    // the prefetch thread sleeps on this one, the calling thread on `ready` (neither may take a core
+    // from the workers)
     if ((e = hipEventCreateWithFlags(&c->freed[s], hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
       return fail(e, "hipEventCreate");
   }
