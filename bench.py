@@ -423,7 +423,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         cm = ctx.dos_calibrate()
         cm.fp32_arrays = 3 if rule == "adamw" else 2    # Adagrad, RMSProp stage p and v only
         log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
-            f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (ring-sized, optimistic)")
+            f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (stand-alone)")
     link = (cm.h2d_Bps, cm.d2h_Bps)
     calibrated = (cm.h2d_Bps, cm.d2h_Bps, cm.gpu_params_per_s, cm.cpu_params_per_s, cm.downscale_params_per_s,
                   cm.launch_overhead_s)

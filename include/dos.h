@@ -298,7 +298,9 @@ dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, c
 
 /* Measures the rates of dos_cost_model on this machine with the context's own
  * slots, streams and worker threads: pinned copies each way under duplex load,
- * the device kernel over one slot, the host update over the upload ring. */
+ * the device kernel over one slot, the host update over a temporary 1.9 GB host
+ * buffer (larger than the caches; allocated and freed inside the call, which is
+ * not part of the update phase). */
 dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 
 /* Timeline of the GPU lane of the context's last phase (contexts created with

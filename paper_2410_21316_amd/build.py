@@ -16,7 +16,10 @@ LIB = os.path.join(HERE, "libdos.so")
 # -ffp-contract=off, correctly rounded divide/sqrt and kept denormals make every
 # source-level float operation one IEEE binary32 operation on device and host.
 # Packed FP32 instructions are switched off for the device pass.
-COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math", "-pthread",
+# -fno-math-errno changes no arithmetic: it lets sqrtf become the (correctly rounded)
+# square-root instruction without a libm call for errno, which is what allows the host
+# update loop to be vectorised at all.
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math", "-fno-math-errno", "-pthread",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-fhip-fp32-correctly-rounded-divide-sqrt",
           "-fno-gpu-flush-denormals-to-zero", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
