@@ -440,7 +440,11 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
         samp = [[take(t, idxs[i]) for t in state.state(i)] + [np.zeros(idxs[i].numel(), np.uint16)]
                 for i in range(len(sizes))]
     for step in range(1, warmup + steps + 1):
-        plan = make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp, cpu_only)
+        # with feedback on, the first warm-up phase runs on the host cores alone: together with the staged
+        # phases that follow it tells the cost model what staging takes away from the host lane
+        probe_all_cpu = adapt and schedule == "balanced" and step == 1 and warmup >= 2 and not residents_max
+        plan = make_plan(dos, "all_cpu" if probe_all_cpu else schedule, cm, sizes, budget_bytes, residents_max, bpp,
+                         cpu_only)
         state.place(plan.targets, plan.residents, spill_all_grads=spill_grads)
         if fresh_grads or step == 1:
             state.fill_grads(step, **gkw)

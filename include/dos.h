@@ -155,6 +155,15 @@ typedef struct dos_cost_model {
   double launch_overhead_s;
   int32_t fp32_arrays; /* FP32 state arrays staged per subgroup: 3 (p, m, v; also
                           meant by 0) or 2 (p, v: Adagrad, RMSProp)               */
+  double cpu_cost_per_dma_byte; /* host-update work, in parameters, that one byte staged
+                          through the GPU lane (either direction) takes away from the
+                          host lane: both lanes share the host's memory system (the
+                          paper's CPU-cores-per-GPU study, Section 5.4, observes the
+                          same contention).  The host lane is priced as
+                          (N_C + cost * staged bytes) / cpu_params_per_s; 0 = the lanes
+                          do not disturb each other.  Above 1 / (2 * 4 * fp32_arrays)
+                          staging a subgroup costs the host lane more than it saves.    */
+  double fit[5];       /* running sums of dos_cost_model_observe; zero-initialise      */
 } dos_cost_model;
 
 enum { DOS_PLAN_STRIDE = 0, DOS_PLAN_BALANCED = 1 };
@@ -312,15 +321,19 @@ dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
  * had into *n_pieces (0 when nothing was timed). */
 dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pieces, int32_t* n_pieces);
 
-/* Replaces the host-update rate and the link rates of `cm` by what the phase that
- * produced `st` actually reached.  Host lane: parameters / lane time.  Link, when
- * the context profiles: bytes / summed copy time per direction, where the
- * host-to-device direction also counts the 16-bit upload bytes that moved while
- * prefetches were busy (the model charges them to that direction), and both
- * rates are then lowered by a common factor until the model reproduces the
- * measured GPU-lane time; without profiling: bytes / lane time as an upper bound
- * on the time (rates only drop).  Call it after every phase and re-plan: the
- * plan then tracks contention between the two lanes. */
+/* Feeds what the phase that produced `st` actually reached back into `cm`.
+ * Host lane: its time is fitted as (N_C + cost * staged bytes) / cpu_params_per_s
+ * over the phases seen so far (older ones fade), which separates the host cores'
+ * own rate from what the GPU lane's traffic takes away from them as soon as two
+ * phases with different splits have been seen; until then cpu_cost_per_dma_byte
+ * keeps its value and only the rate moves.  Link, when the context profiles:
+ * bytes / summed copy time per direction, where the host-to-device direction also
+ * counts the 16-bit upload bytes that moved while prefetches were busy (the model
+ * charges them to that direction), and both rates are then lowered by a common
+ * factor until the model reproduces the measured GPU-lane time; without
+ * profiling: bytes / lane time as an upper bound on the time (rates only drop).
+ * Call it after every phase and re-plan: the plan then tracks contention between
+ * the two lanes, and falls back to the host cores alone where staging does not pay. */
 dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st);
 
 /* ---- utilities ------------------------------------------------------------ */

@@ -39,7 +39,8 @@ class dos_launch_cfg(C.Structure):
 class dos_cost_model(C.Structure):
     _fields_ = [("h2d_Bps", C.c_double), ("d2h_Bps", C.c_double), ("gpu_params_per_s", C.c_double),
                 ("cpu_params_per_s", C.c_double), ("downscale_params_per_s", C.c_double),
-                ("launch_overhead_s", C.c_double), ("fp32_arrays", C.c_int32)]
+                ("launch_overhead_s", C.c_double), ("fp32_arrays", C.c_int32),
+                ("cpu_cost_per_dma_byte", C.c_double), ("fit", C.c_double * 5)]
 
 
 class dos_plan(C.Structure):
@@ -225,9 +226,9 @@ class Plan:
 
 
 def cost_model(h2d_Bps, d2h_Bps, gpu_params_per_s, cpu_params_per_s, downscale_params_per_s=0.0,
-               launch_overhead_s=0.0, fp32_arrays=3) -> dos_cost_model:
+               launch_overhead_s=0.0, fp32_arrays=3, cpu_cost_per_dma_byte=0.0) -> dos_cost_model:
     return dos_cost_model(h2d_Bps, d2h_Bps, gpu_params_per_s, cpu_params_per_s,
-                          downscale_params_per_s, launch_overhead_s, int(fp32_arrays))
+                          downscale_params_per_s, launch_overhead_s, int(fp32_arrays), float(cpu_cost_per_dma_byte))
 
 
 def dos_plan_subgroups(cm: dos_cost_model, sizes, gpu_budget_bytes: int, mode: int = DOS_PLAN_BALANCED,

@@ -27,7 +27,8 @@ struct Cost {
 double state_bytes_of(const dos_cost_model& cm) { return cm.fp32_arrays == 2 ? 8.0 : 12.0; }
 
 bool valid_cost_model(const dos_cost_model* cm) {
-  return cm && (cm->fp32_arrays == 0 || cm->fp32_arrays == 2 || cm->fp32_arrays == 3) && cm->h2d_Bps > 0 && cm->d2h_Bps > 0 && cm->gpu_params_per_s > 0 &&
+  return cm && (cm->fp32_arrays == 0 || cm->fp32_arrays == 2 || cm->fp32_arrays == 3) &&
+         cm->cpu_cost_per_dma_byte >= 0 && isfinite(cm->cpu_cost_per_dma_byte) && cm->h2d_Bps > 0 && cm->d2h_Bps > 0 && cm->gpu_params_per_s > 0 &&
          cm->cpu_params_per_s > 0 && cm->downscale_params_per_s >= 0 && cm->launch_overhead_s >= 0 &&
          isfinite(cm->h2d_Bps) && isfinite(cm->d2h_Bps) && isfinite(cm->gpu_params_per_s) &&
          isfinite(cm->cpu_params_per_s) && isfinite(cm->downscale_params_per_s) &&
@@ -58,7 +59,8 @@ Cost evaluate(const dos_cost_model& cm, const uint64_t* sizes, const uint8_t* ta
   const double sb = state_bytes_of(cm);
   const double h2d_bytes = sb * NG + 2.0 * NC, d2h_bytes = sb * NG;
   const double t_h2d = h2d_bytes / cm.h2d_Bps, t_d2h = d2h_bytes / cm.d2h_Bps;
-  const double t_cpu = NC / cm.cpu_params_per_s;
+  // the staged traffic (both directions) takes host memory bandwidth from the host update
+  const double t_cpu = (NC + cm.cpu_cost_per_dma_byte * 2.0 * sb * NG) / cm.cpu_params_per_s;
   const double t_gpu = (NG + NR) / cm.gpu_params_per_s + cm.launch_overhead_s * (cg + cr);
   double lane;
   if (cg == 0) {
@@ -239,7 +241,34 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
 // alone -- the paper observes the same in its CPU-cores-per-GPU study, Section 5.4).
 extern "C" dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st) {
   if (!cm || !st) return DOS_EINVAL;
-  if (st->params_cpu > 0 && st->cpu_lane_s > 0.0) cm->cpu_params_per_s = (double)st->params_cpu / st->cpu_lane_s;
+  if (st->params_cpu > 0 && st->cpu_lane_s > 0.0) {
+    // Host lane: least-squares fit of  lane time = a * N_C + b * staged bytes  over the phases
+    // seen so far (weights fade by a quarter per phase); rate = 1/a, cost per byte = b/a.
+    const double x1 = (double)st->params_cpu * 1e-9;
+    const double staged_bytes = std::max(0.0, st->h2d_bytes - 2.0 * (double)st->params_cpu) + st->d2h_bytes;
+    const double x2 = staged_bytes * 1e-9, y = st->cpu_lane_s;
+    double* f = cm->fit;  // sums of x1*x1, x1*x2, x2*x2, x1*y, x2*y
+    for (int i = 0; i < 5; ++i) f[i] = isfinite(f[i]) ? f[i] * 0.75 : 0.0;
+    f[0] += x1 * x1; f[1] += x1 * x2; f[2] += x2 * x2; f[3] += x1 * y; f[4] += x2 * y;
+    const double det = f[0] * f[2] - f[1] * f[1];
+    bool fitted = false;
+    if (f[2] > 0.0 && det > 1e-4 * f[0] * f[2]) {  // phases with different splits have been seen
+      const double a = (f[3] * f[2] - f[4] * f[1]) / det, b = (f[4] * f[0] - f[3] * f[1]) / det;
+      if (a > 0.0 && b >= 0.0) {
+        cm->cpu_params_per_s = 1e9 / a;
+        // a byte of traffic cannot displace much more host work than the update's own bytes per
+        // parameter allow (about 1/32); a larger fit is measurement noise on nearly equal splits
+        cm->cpu_cost_per_dma_byte = std::min(b / a, 0.125);
+        fitted = true;
+      } else if (a > 0.0 && f[3] > 0.0) {  // staging did not slow the host lane down: no cost
+        cm->cpu_params_per_s = 1e9 * f[0] / f[3];
+        cm->cpu_cost_per_dma_byte = 0.0;
+        fitted = true;
+      }
+    }
+    // one split only (or a fit that makes no sense): the cost keeps its value, the rate explains this phase
+    if (!fitted) cm->cpu_params_per_s = ((double)st->params_cpu + cm->cpu_cost_per_dma_byte * staged_bytes) / y;
+  }
   if (st->params_gpu > 0 && st->h2d_busy_s > 0.0 && st->d2h_busy_s > 0.0) {
     // summed copy durations (DOS_CTX_PROFILE) give the rate each direction reached while busy.
     // The 16-bit uploads of the host lane share the host-to-device direction with the

@@ -286,6 +286,73 @@ def test_two_array_rules_move_eight_bytes_per_parameter():
         dos.dos_plan_subgroups(bad, sizes, 4 * 10**9)
 
 
+def _phase(n_c, n_g, u0, beta, t_gpu_lane=None):
+    """Stats of a phase on a machine whose host lane takes (N_C + beta * staged bytes) / u0."""
+    st = dos.dos_phase_stats()
+    st.params_cpu, st.params_gpu = int(n_c), int(n_g)
+    st.h2d_bytes = 12.0 * n_g + 2.0 * n_c
+    st.d2h_bytes = 12.0 * n_g
+    st.cpu_lane_s = (n_c + beta * 24.0 * n_g) / u0
+    st.h2d_busy_s = st.d2h_busy_s = -1.0
+    st.gpu_lane_s = t_gpu_lane if t_gpu_lane is not None else st.cpu_lane_s
+    return st
+
+
+def test_observe_separates_the_host_rate_from_what_staging_costs_it():
+    """Both lanes share the host's memory system (Section 5.4 of the paper sees the same contention).
+    From phases with different splits the feedback recovers the host cores' own rate and the host work
+    that a staged byte takes away; the planner then stops staging where it costs more than it saves."""
+    u0, beta = 12.0e9, 0.035
+    cm = dos.cost_model(56e9, 48e9, 230e9, 15e9)                 # calibrated stand-alone: optimistic
+    dos.dos_cost_model_observe(cm, _phase(9.0e9, 4.0e9, u0, beta))
+    # one split: the cost keeps its value (0), the rate alone explains the phase
+    assert cm.cpu_cost_per_dma_byte == 0.0
+    assert cm.cpu_params_per_s == pytest.approx(9.0e9 / ((9.0e9 + beta * 96e9) / u0))
+    dos.dos_cost_model_observe(cm, _phase(11.0e9, 2.0e9, u0, beta))
+    assert cm.cpu_params_per_s == pytest.approx(u0, rel=1e-6)
+    assert cm.cpu_cost_per_dma_byte == pytest.approx(beta, rel=1e-6)
+    # more phases of the same machine keep the fit where it is, also when the split no longer changes
+    for _ in range(6):
+        dos.dos_cost_model_observe(cm, _phase(11.0e9, 2.0e9, u0, beta))
+    assert cm.cpu_params_per_s == pytest.approx(u0, rel=1e-3) and cm.cpu_cost_per_dma_byte == pytest.approx(beta, rel=1e-3)
+    # an all-CPU phase fits the same line
+    dos.dos_cost_model_observe(cm, _phase(13.0e9, 0.0, u0, beta))
+    assert cm.cpu_params_per_s == pytest.approx(u0, rel=1e-3)
+    # the machine changes (another tenant takes memory bandwidth): the fit follows within a few phases
+    for k in range(12):
+        dos.dos_cost_model_observe(cm, _phase(10.0e9 + 1e9 * (k % 3), 3.0e9 - 1e9 * (k % 3), 9.0e9, 0.02))
+    assert cm.cpu_params_per_s == pytest.approx(9.0e9, rel=0.02) and cm.cpu_cost_per_dma_byte == pytest.approx(0.02, rel=0.1)
+
+
+def test_planner_prices_contention_and_falls_back_to_the_host_cores():
+    sizes = [100_000_000] * 40
+    tg = [1 if i % 4 == 0 else 0 for i in range(40)]
+    ng, nc = 1.0e9, 3.0e9
+    cm = dos.cost_model(56e9, 48e9, 230e9, 12e9, cpu_cost_per_dma_byte=0.03)
+    pred, low = dos.dos_plan_cost(cm, sizes, tg, 3, None, 16 << 20)
+    lead = 12.0 * (16 << 20) / 56e9 + (16 << 20) / 230e9
+    want = max((nc + 0.03 * 24.0 * ng) / 12e9, (12 * ng + 2 * nc) / 56e9, lead + 12 * ng / 48e9)
+    assert pred == pytest.approx(want) and low == pytest.approx(max((12 * ng + 2 * nc) / 56e9, 12 * ng / 48e9))
+    # a staged subgroup takes 24 B/param of traffic: at more than 1/24 parameters per byte it costs the host
+    # lane more work than it removes, and the balanced plan keeps everything on the host cores
+    for cost, staged in ((0.0, True), (0.02, True), (0.045, False), (0.2, False)):
+        cm = dos.cost_model(56e9, 48e9, 230e9, 12e9, cpu_cost_per_dma_byte=cost)
+        plan = dos.dos_plan_subgroups(cm, sizes, 4 * 10**9)
+        assert (sum(plan.targets) > 0) == staged, cost
+        if not staged:
+            assert plan.c.predicted_s == pytest.approx(4.0e9 / 12e9)
+    # below that point a growing cost slows the host lane down, so the balance moves towards the GPU and
+    # the predicted time grows
+    plans = [dos.dos_plan_subgroups(dos.cost_model(56e9, 48e9, 230e9, 6e9, cpu_cost_per_dma_byte=c), sizes, 4 * 10**9)
+             for c in (0.0, 0.01, 0.02, 0.03)]
+    counts = [sum(pl.targets) for pl in plans]
+    times = [pl.c.predicted_s for pl in plans]
+    assert counts == sorted(counts) and counts[0] > 0 and times == sorted(times) and times[0] < times[-1]
+    assert times[-1] < 4.0e9 / 6e9                     # still better than the host cores alone
+    with pytest.raises(dos.DosError):
+        dos.dos_plan_subgroups(dos.cost_model(56e9, 48e9, 230e9, 6e9, cpu_cost_per_dma_byte=-0.1), sizes, 4 * 10**9)
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_balanced_plan_invariants_on_random_machines(seed):
     """Whatever the rates: the balanced plan is never worse (by its own estimate)
