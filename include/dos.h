@@ -115,7 +115,9 @@ typedef struct dos_launch_cfg {
  * Fused update (hp->optimizer; AdamW unless said otherwise) over one subgroup
  * whose arrays are all device memory.
  * Asynchronous on hip_stream (a hipStream_t, NULL = the default stream); no
- * allocation, no synchronisation.  HBM traffic is 28 bytes per element (reads
+ * allocation, no synchronisation, so a stream under HIP graph capture records
+ * just the kernel launch (the per-step scalars are kernel arguments: a replay
+ * repeats the captured step number).  HBM traffic is 28 bytes per element (reads
  * 4+4+4+2, writes 4+4+4+2; 20 bytes for the rules without a first moment).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
  * state_loc/grad_loc not DOS_DEVICE is DOS_ESTATE), DOS_EALIGN, DOS_EHIP. */
 dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);

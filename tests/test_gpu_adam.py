@@ -191,6 +191,39 @@ def test_errors_leave_device_state_untouched(hp):
         assert a.tobytes() == b.tobytes()
 
 
+@pytest.mark.parametrize("optimizer", ["adamw", "adagrad"])
+def test_can_be_captured_in_a_hip_graph_and_replayed(optimizer, hp):
+    """dos_adam_step allocates nothing and synchronises nothing, so a stream that is being captured
+    records just the kernel launch.  The graph is replayed four times with fresh gradients copied into
+    the same buffer and eager work between the replays; every replay is checked against the oracle (the
+    per-step scalars are kernel arguments, so each replay is the captured step number again)."""
+    n = 300_007
+    sg = DeviceSubgroup(n, S.BASE_SEED + 21)
+    st = list(sg.host_copy())
+    state = [st[0], st[1], st[2], st[4]]
+    h = dos.hparams(step=5, optimizer=optimizer, **hp)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    sg.set_grads(1)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        dos.dos_adam_step(sg.desc, h, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    # capture records, it does not run: the state is still the initial one
+    assert sg.host_copy()[0].tobytes() == state[0].tobytes()
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for replay in range(1, 5):
+        sg.set_grads(replay, zero_pct=1.0)
+        scratch.add_(1.0)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        p, m, v, g, lp = sg.host_copy()
+        oracle_step(state, g, hp, 5, optimizer=optimizer)
+        assert_parity(f"{optimizer} graph replay {replay}", (p, m, v), state[:3], lp, state[3])
+    assert float(scratch[0]) == 4.0
+
+
 def test_runs_on_a_side_stream_without_synchronising(hp):
     side = torch.cuda.Stream()
     sg = DeviceSubgroup(1 << 18, S.BASE_SEED + 1)
