@@ -27,6 +27,9 @@ LINK_NOMINAL_GBPS = 64.0        # PCIe Gen5 x16 per direction, nominal
 BYTES_PER_PARAM = 28            # reads 4+4+4+2, writes 4+4+4+2
 
 
+UPLOAD_FLAGS = 0                # set in main(): how the host lane sends the 16-bit parameters to the device
+
+
 def profiled_traffic(name):
     """HBM bytes per launch from the committed rocprofv3 counter summary (None if absent)."""
     try:
@@ -417,7 +420,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
     bpp = 14 if spill_grads else 12
     plan = dos.dos_plan_subgroups(probe_cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max, bpp, cpu_only)
-    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE,
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE | UPLOAD_FLAGS,
                          stage_grads=spill_grads)
     if cm is None:
         cm = ctx.dos_calibrate()
@@ -505,7 +508,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
            "h2d_frac_of_measured_link": best["h2d_GBps"] * 1e9 / link[0],
            "d2h_frac_of_measured_link": best["d2h_GBps"] * 1e9 / link[1],
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
-           "host_threads": host_threads, "sample_mismatches_vs_oracle": mism, "steps": results,
+           "host_threads": host_threads, "uploads": {0: "pull", 2: "dma", 8: "direct"}[UPLOAD_FLAGS],
+           "sample_mismatches_vs_oracle": mism, "steps": results,
            "calibrated": calibrated}
     ctx.close()
     ctx._keep[1].free()          # the pinned upload ring
@@ -668,6 +672,10 @@ def main():
                     help="comma list of extra workloads (c1, c3, c4, rules = Adagrad and RMSProp on the c2 shape) "
                          "or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
+    ap.add_argument("--upload", default="auto", choices=["auto", "direct", "pull", "dma"],
+                    help="how the host lane of the interleaved workloads sends the 16-bit parameters to the device: "
+                         "direct = host stores through the PCIe BAR (auto picks it when the device memory is mapped "
+                         "into the host's address space), pull = copy kernel reading a pinned ring, dma = hipMemcpyAsync")
     ap.add_argument("--rule", default="adamw", choices=["adamw", "adagrad", "rmsprop"],
                     help="update rule of the interleaved workload c4 (the primary workload is always AdamW)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -693,6 +701,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dos.load()
+    global UPLOAD_FLAGS
+    upload = args.upload
+    if upload == "auto":
+        upload = "direct" if dos.dos_device_large_bar(0) else "pull"
+    UPLOAD_FLAGS = {"direct": dos.DOS_CTX_UPLOAD_DIRECT, "dma": dos.DOS_CTX_UPLOAD_DMA, "pull": 0}[upload]
+    log(f"[bench] 16-bit uploads of the host lane: {upload}")
     if args.host_threads <= 0:
         args.host_threads = len(os.sched_getaffinity(0))
     res = bench_c2(args, dos, torch, np)

@@ -229,6 +229,13 @@ enum {
   DOS_CTX_PROFILE = 1,    /* time every copy and kernel with events                            */
   DOS_CTX_UPLOAD_DMA = 2, /* send 16-bit uploads with hipMemcpyAsync instead of the default
                              pull-copy kernel (DMA uploads queue behind the bulk prefetches)  */
+  DOS_CTX_UPLOAD_DIRECT = 8, /* the host workers write the 16-bit parameters of CPU-planned
+                             subgroups straight into p_lp -- device memory, written by the host
+                             cores through the PCIe BAR -- instead of into the pinned ring: no
+                             ring, no upload kernels, and 4 bytes per parameter less host-memory
+                             traffic.  Needs a device whose whole memory is mapped into the host's
+                             address space (dos_device_large_bar); creation fails with DOS_ESTATE
+                             otherwise.  pinned_stage may then be NULL                         */
   DOS_CTX_SPIN_WAIT = 4   /* the two threads that drive the GPU lane spin while they wait for
                              a slot or a piece instead of sleeping (takes cores from the host
                              workers)                                                         */
@@ -339,6 +346,11 @@ dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pie
 dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st);
 
 /* ---- utilities ------------------------------------------------------------ */
+
+/* *yes = 1 when the whole memory of HIP device `device` is mapped into the host's
+ * address space (resizable / large PCIe BAR), so that host cores can write device
+ * memory directly: what DOS_CTX_UPLOAD_DIRECT needs. */
+dos_status dos_device_large_bar(int32_t device, int32_t* yes);
 
 /* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */
 dos_status dos_pinned_alloc(void** out, uint64_t bytes);

@@ -18,6 +18,7 @@ DOS_PLAN_STRIDE, DOS_PLAN_BALANCED = 0, 1
 DOS_CTX_PROFILE = 1
 DOS_CTX_UPLOAD_DMA = 2
 DOS_CTX_SPIN_WAIT = 4
+DOS_CTX_UPLOAD_DIRECT = 8
 
 
 class dos_subgroup(C.Structure):
@@ -94,6 +95,7 @@ SIGNATURES = {
     "dos_calibrate": (C.c_int, [C.c_void_p, C.POINTER(dos_cost_model)]),
     "dos_ctx_last_timeline": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]),
     "dos_cost_model_observe": (C.c_int, [C.POINTER(dos_cost_model), C.POINTER(dos_phase_stats)]),
+    "dos_device_large_bar": (C.c_int, [C.c_int32, C.POINTER(C.c_int32)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
     "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
@@ -257,6 +259,12 @@ def dos_plan_cost(cm: dos_cost_model, sizes, targets, n_slots: int, residents=No
 
 def dos_cost_model_observe(cm: dos_cost_model, st: dos_phase_stats) -> None:
     check(load().dos_cost_model_observe(C.byref(cm), C.byref(st)), "dos_cost_model_observe")
+
+
+def dos_device_large_bar(device: int = 0) -> bool:
+    yes = C.c_int32()
+    check(load().dos_device_large_bar(int(device), C.byref(yes)), "dos_device_large_bar")
+    return bool(yes.value)
 
 
 def dos_pinned_alloc(nbytes: int) -> int:

@@ -128,6 +128,14 @@ void rmsprop_block(float* __restrict__ p, float* __restrict__ v, const uint16_t*
 
 }  // namespace
 
+void store_fence() {
+#if defined(__x86_64__) || defined(__i386__)
+  __builtin_ia32_sfence();
+#else
+  __atomic_thread_fence(__ATOMIC_SEQ_CST);
+#endif
+}
+
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                      const AdamScalars& s) {
   if (s.opt == DOS_OPT_ADAGRAD) adagrad_block(p, v, g, p_lp, n, s);

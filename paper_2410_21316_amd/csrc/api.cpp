@@ -38,6 +38,19 @@ dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hi
   return dos_adam_step_cfg(sg, hp, hip_stream, nullptr);
 }
 
+dos_status dos_device_large_bar(int32_t device, int32_t* yes) {
+  if (!yes) return DOS_EINVAL;
+  int v = 0;
+  hipError_t e = hipDeviceGetAttribute(&v, hipDeviceAttributeIsLargeBar, device);
+  if (e != hipSuccess) {
+    dos::note_hip_error((int)e, "hipDeviceGetAttribute");
+    (void)hipGetLastError();
+    return DOS_EHIP;
+  }
+  *yes = v ? 1 : 0;
+  return DOS_OK;
+}
+
 dos_status dos_pinned_alloc(void** out, uint64_t bytes) {
   if (!out || bytes == 0) return DOS_EINVAL;
   *out = nullptr;

@@ -49,6 +49,9 @@ dos_status launch_probe_traffic(const dos_subgroup* sg, int mode, int lds_bytes,
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                      const AdamScalars& s);
 
+// Drains the calling core's write-combining buffers (x86 sfence).
+void store_fence();
+
 // Records the text of a failed HIP call for dos_last_hip_error().
 void note_hip_error(int code, const char* what);
 

@@ -101,6 +101,7 @@ struct dos_ctx {
   struct alignas(64) LaneTimes { double compute = 0, wait = 0, enqueue = 0; };
   std::vector<LaneTimes> lane_times;  // one per worker, reset every phase
   std::atomic<bool> cpu_started{false};
+  std::atomic<uint32_t> direct_sink{0};  // keeps the read-backs of the direct uploads alive
   // prefetch thread of the GPU lane: it enqueues the host-to-device copies, the
   // calling thread the kernels and the flushes (an enqueue of a copy can block its
   // caller while earlier copies of the same direction are in flight; with one thread
@@ -179,12 +180,24 @@ void worker_main(dos_ctx* c, int tid) {
     const int64_t total = (int64_t)chunks.size();
     dos_ctx::LaneTimes& lt = c->lane_times[tid];
     lt = dos_ctx::LaneTimes();
+    const volatile uint16_t* last_direct = nullptr;  // last word this worker wrote into device memory
     for (;;) {
       const int64_t ci = c->next_chunk.fetch_add(1);
       if (ci >= total || c->job_error.load()) break;
       if (!c->cpu_started.exchange(true)) c->cpu_first = clk::now();
       const Chunk& ch = chunks[ci];
       const dos_subgroup& sg = c->job_sgs[ch.sg];
+      if (c->flags & DOS_CTX_UPLOAD_DIRECT) {
+        // the 16-bit parameters go straight into the device model: p_lp is device memory that this
+        // core writes through the PCIe BAR (posted writes, combined into whole lines on the way)
+        const auto td0 = clk::now();
+        uint16_t* dst = sg.p_lp + ch.off;
+        dos::host_adam_range(sg.p + ch.off, sg.m ? sg.m + ch.off : nullptr, sg.v + ch.off, sg.g + ch.off, dst,
+                             ch.cnt, c->job_scalars);
+        last_direct = dst + (ch.cnt - 1);
+        lt.compute += secs(td0, clk::now());
+        continue;
+      }
       const int r = (int)(ci % c->ring_n);
       // the ring entry is free once the upload of chunk ci - ring_n has landed
       const auto tw0 = clk::now();
@@ -223,6 +236,14 @@ void worker_main(dos_ctx* c, int tid) {
       lt.wait += secs(tw0, tw1);
       lt.compute += secs(tw1, tw2);
       lt.enqueue += secs(tw2, tw3);
+    }
+    if (last_direct) {
+      // The writes through the BAR are posted.  A store fence drains this core's write-combining
+      // buffers, and reading one of the written words back cannot complete before the writes ahead
+      // of it have reached the device: after this, work launched on the GPU sees them.
+      std::atomic_thread_fence(std::memory_order_seq_cst);
+      dos::store_fence();
+      c->direct_sink.fetch_add(*last_direct, std::memory_order_relaxed);
     }
     {
       std::lock_guard<std::mutex> lk(c->mu);
@@ -389,6 +410,15 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     (void)hipGetLastError();
     return DOS_EHIP;
   }
+  if (cfg->flags & DOS_CTX_UPLOAD_DIRECT) {
+    // host cores may write device memory only where all of it is mapped into the host's address space
+    int large_bar = 0;
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, cfg->device) != hipSuccess) {
+      (void)hipGetLastError();
+      return DOS_EHIP;
+    }
+    if (!large_bar) return DOS_ESTATE;
+  }
   dos_ctx* c = new dos_ctx();
   c->device = cfg->device;
   c->flags = cfg->flags;
@@ -494,7 +524,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
     if (plan->target[i] == DOS_ON_CPU) {
       // the host cores read and write it in place: pinned or pageable, but not device memory
       if (sg.state_loc == DOS_DEVICE || sg.grad_loc == DOS_DEVICE) return DOS_ESTATE;
-      if (c->ring_n < 2) return DOS_EBUDGET;
+      if (c->ring_n < 2 && !(c->flags & DOS_CTX_UPLOAD_DIRECT)) return DOS_EBUDGET;
       for (uint64_t off = 0; off < sg.n; off += c->chunk_params)
         chunks.push_back({i, off, std::min(c->chunk_params, sg.n - off)});
       params_cpu += sg.n;

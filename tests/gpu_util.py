@@ -195,15 +195,15 @@ def make_context(n_slots, slot_params, host_threads=4, chunk_params=1 << 16, rin
     bpp = 14 if stage_grads else 12
     slot_mem = torch.empty(max(n_slots, 1) * bpp * slot_params + 256, dtype=torch.uint8, device=device)
     base = round_up(slot_mem.data_ptr(), 256)
-    stage = Pinned(ring_chunks * chunk_params * 2)
+    stage = Pinned(ring_chunks * chunk_params * 2) if ring_chunks else None     # 0: no upload ring at all
     cfg = dos.dos_ctx_config()
     cfg.slot_mem = base if n_slots else None
     cfg.slot_bytes = n_slots * bpp * slot_params
     cfg.slot_params = slot_params
     cfg.n_slots = n_slots
     cfg.host_threads = host_threads
-    cfg.pinned_stage = stage.ptr
-    cfg.pinned_stage_bytes = stage.nbytes
+    cfg.pinned_stage = stage.ptr if stage else None
+    cfg.pinned_stage_bytes = stage.nbytes if stage else 0
     cfg.upload_chunk_params = chunk_params
     cfg.flags = flags
     cfg.device = 0

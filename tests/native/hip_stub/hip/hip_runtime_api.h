@@ -25,6 +25,13 @@ inline double stub_now_ms() {
 }
 inline hipError_t hipSetDevice(int d) { return d == 0 ? hipSuccess : hipErrorInvalidDevice; }
 inline hipError_t hipGetLastError() { return hipSuccess; }
+enum hipDeviceAttribute_t { hipDeviceAttributeIsLargeBar = 1 };
+// the stand-in device's memory is host memory: the host can always write it
+inline hipError_t hipDeviceGetAttribute(int* v, hipDeviceAttribute_t, int d) {
+  if (d != 0) return hipErrorInvalidDevice;
+  *v = 1;
+  return hipSuccess;
+}
 inline const char* hipGetErrorString(hipError_t) { return "stub"; }
 inline hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned) {
   *s = reinterpret_cast<hipStream_t>(new int(0));

@@ -98,6 +98,13 @@ int main() {
     cfg.pinned_stage_bytes = (uint64_t)ring * chunk * 2;
     cfg.upload_chunk_params = chunk;
     cfg.flags = (it % 2) ? DOS_CTX_PROFILE : 0;
+    if (it % 4 >= 2) {                       // direct uploads: no ring at all
+      cfg.flags |= DOS_CTX_UPLOAD_DIRECT;
+      if (it % 8 >= 4) {
+        cfg.pinned_stage = nullptr;
+        cfg.pinned_stage_bytes = 0;
+      }
+    }
     dos_ctx* ctx = nullptr;
     if (dos_ctx_create(&ctx, &cfg) != DOS_OK) return fail("dos_ctx_create failed");
     dos_plan plan{};

@@ -33,6 +33,8 @@ def run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=3, res
             st.check(f"{optimizer} step {step} targets {targets} slots {n_slots}x{slot_params}")
     finally:
         ctx.close()
+        if ctx._keep[1] is not None:
+            ctx._keep[1].free()
         st.free()
     return stats
 
@@ -63,6 +65,56 @@ def test_random_plans_slots_pieces_and_orders(case, hp):
     run_phase_case(sizes, targets, order, n_slots, slot_params, hp, steps=2, grad_on_device=grad_dev,
                    host_threads=rng.choice([1, 3, 8]), chunk_params=rng.choice([1 << 12, 1 << 16]),
                    ring_chunks=rng.choice([2, 3, 9]), seed=S.BASE_SEED + case, zero_pct=5.0, heavy_tail=True)
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_direct_uploads_through_the_bar(case, hp):
+    """DOS_CTX_UPLOAD_DIRECT: the host workers write the 16-bit parameters of CPU-planned subgroups
+    straight into the device model (host stores through the PCIe BAR), with or without an upload ring
+    in the context; same bits as the oracle, and the device sees them as soon as the phase returns."""
+    if not dos.dos_device_large_bar(0):
+        pytest.skip("the device memory is not mapped into the host's address space")
+    rng = random.Random(2000 + case)
+    sizes = SIZES[:]
+    rng.shuffle(sizes)
+    targets = [rng.random() < 0.4 for _ in sizes]
+    order = list(range(len(sizes)))
+    rng.shuffle(order)
+    optimizer = ["adamw", "adagrad", "rmsprop"][case % 3]
+    stats = run_phase_case(sizes, targets, order, rng.choice([1, 3]), rng.choice([1 << 16, 1 << 20]), hp, steps=3,
+                           grad_on_device=[t and rng.random() < 0.5 for t in targets],
+                           host_threads=rng.choice([1, 4, 8]), chunk_params=rng.choice([1 << 12, 1 << 16]),
+                           ring_chunks=rng.choice([0, 3]), seed=S.BASE_SEED + 50 + case, optimizer=optimizer,
+                           flags=dos.DOS_CTX_UPLOAD_DIRECT | (dos.DOS_CTX_PROFILE if case % 2 else 0),
+                           zero_pct=5.0, heavy_tail=True)
+    assert stats.params_cpu == sum(n for n, t in zip(sizes, targets) if not t)
+    assert stats.cpu_wait_s == 0.0 and stats.cpu_enqueue_s == 0.0        # no ring, no upload kernels
+
+
+def test_direct_uploads_are_visible_to_kernels_that_cached_the_old_model(hp):
+    """A kernel reads the 16-bit model (its lines may sit in the GPU's caches), the phase then rewrites it
+    from the host cores through the BAR, and a kernel launched afterwards must read the new values."""
+    if not dos.dos_device_large_bar(0):
+        pytest.skip("the device memory is not mapped into the host's address space")
+    sizes = [300_000, 150_016]
+    st = OffloadedState(sizes, S.BASE_SEED + 60)
+    ctx = make_context(0, 1 << 16, 4, ring_chunks=0, flags=dos.DOS_CTX_UPLOAD_DIRECT)
+    plan = dos.Plan.manual([0, 0], None, 0, 0)
+    try:
+        for step in range(1, 6):
+            before = [st.dev[i]["lp"].view(torch.int16).to(torch.int64).sum().item() for i in range(2)]  # caches it
+            st.set_grads(step)
+            ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, **hp))
+            st.oracle_step(hp, step)
+            for i in range(2):
+                # a reduction kernel, not a copy engine, reads the model right after the phase
+                got = st.dev[i]["lp"].view(torch.int16).to(torch.int64).sum().item()
+                want = int(st.ref[i][3].view(np.int16).astype(np.int64).sum())
+                assert got == want and (step == 1 or got != before[i])
+            st.check(f"direct step {step}")
+    finally:
+        ctx.close()
+        st.free()
 
 
 @pytest.mark.parametrize("optimizer", ["adagrad", "rmsprop"])
