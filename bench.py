@@ -415,6 +415,10 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
                 f"limit); the other {len(sizes) - state.n_pinned} live in pageable host memory and stay on the host cores")
         sizes = list(state.sizes)
         log(f"[{tag}] built {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
+    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT and own_state:
+        t0 = time.perf_counter()
+        state.map_model_for_host_writes(host_threads)
+        log(f"[{tag}] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
     cpu_only = state.cpu_only if any(state.cpu_only) else None
     # slots first (they decide what the context can do), then calibration, then the plan
     probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
@@ -561,6 +565,8 @@ def bench_ablation(args, dos, torch, np):
     sizes = [100_000_000] * 130
     state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30,
                              pageable_rest=args.full_size)
+    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+        state.map_model_for_host_writes(args.host_threads)
     sizes = list(state.sizes)
     scale = sum(sizes) / 13e9
     budget = int(40 * 10**9 * scale)
@@ -625,6 +631,8 @@ def bench_c5(args, dos, torch, np):
             sizes = [sg_params] * n_keep
         state = W.OffloadedState(sizes, S.BASE_SEED + 5, "cuda:0", pinned_reserve_bytes=1 << 30,
                                  pageable_rest=args.full_size)
+        if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+            state.map_model_for_host_writes(args.host_threads)
         sizes = list(state.sizes)
         if scale is None:
             scale = sum(sizes) / total_nominal

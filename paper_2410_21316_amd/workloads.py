@@ -177,6 +177,14 @@ class OffloadedState:
         self.sgs = arr
         return arr
 
+    def map_model_for_host_writes(self, threads: int = 1):
+        """Touches every page of the device-resident 16-bit model from the host, so that the first phase
+        with direct uploads (host stores through the PCIe BAR) does not pay for mapping those pages."""
+        torch.cuda.synchronize()
+        for lp in self.lp:
+            if lp.numel():
+                dos.dos_host_prefault(lp.data_ptr(), lp.numel() * 2, threads)
+
     def sync_host_grads(self):
         """Spill the gradients the descriptors expect in pinned host memory."""
         for i in range(len(self.sizes)):
