@@ -393,7 +393,7 @@ def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp=12, cpu
 
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
                     cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced",
-                    fresh_grads=True, spill_grads=False, pageable_rest=False, rule="adamw"):
+                    fresh_grads=True, spill_grads=False, pageable_rest=False, rule="adamw", upload_flags=None):
     """Plan + run the interleaved phase on a host-offloaded state; returns a dict.
     fresh_grads=False generates the gradients once and reuses them for every step;
     spill_grads=True keeps every gradient in pinned host memory (GPU-planned subgroups fetch theirs
@@ -403,6 +403,8 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     import dos_synth as S
     hp_kw = dict(S.HPARAMS)
     own_state = state is None
+    if upload_flags is None:
+        upload_flags = UPLOAD_FLAGS
     t0 = time.perf_counter()
     if own_state:
         # leave room for the context's pinned upload ring
@@ -415,7 +417,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
                 f"limit); the other {len(sizes) - state.n_pinned} live in pageable host memory and stay on the host cores")
         sizes = list(state.sizes)
         log(f"[{tag}] built {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
-    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT and own_state:
+    if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT and own_state:
         t0 = time.perf_counter()
         state.map_model_for_host_writes(host_threads)
         log(f"[{tag}] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
@@ -424,7 +426,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
     bpp = 14 if spill_grads else 12
     plan = dos.dos_plan_subgroups(probe_cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max, bpp, cpu_only)
-    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE | UPLOAD_FLAGS,
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE | upload_flags,
                          stage_grads=spill_grads)
     if cm is None:
         cm = ctx.dos_calibrate()
@@ -512,7 +514,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
            "h2d_frac_of_measured_link": best["h2d_GBps"] * 1e9 / link[0],
            "d2h_frac_of_measured_link": best["d2h_GBps"] * 1e9 / link[1],
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
-           "host_threads": host_threads, "uploads": {0: "pull", 2: "dma", 8: "direct"}[UPLOAD_FLAGS],
+           "host_threads": host_threads, "uploads": {0: "pull", 2: "dma", 8: "direct"}[upload_flags],
            "sample_mismatches_vs_oracle": mism, "steps": results,
            "calibrated": calibrated}
     ctx.close()
@@ -544,10 +546,21 @@ def lower_bound_opt(sizes, movable, link, u_gpu, u_cpu, state_bytes, resident_pa
 
 
 def bench_c4(args, dos, torch, np):
+    from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     sizes = [100_000_000] * 130
+    t0 = time.perf_counter()
+    state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30, pageable_rest=True)
+    if state.n_pinned < len(sizes):
+        log(f"[c4] this machine pins only {state.n_pinned} of the {len(sizes)} subgroups (hipHostMalloc limit); the "
+            f"other {len(sizes) - state.n_pinned} live in pageable host memory and stay on the host cores")
+    log(f"[c4] built {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
+    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+        t0 = time.perf_counter()
+        state.map_model_for_host_writes(args.host_threads)
+        log(f"[c4] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
     out = run_interleaved(dos, torch, np, sizes, 40 * 10**9, steps=5, warmup=3, host_threads=args.host_threads,
-                          gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4", pageable_rest=True, rule=args.rule)
+                          gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4", state=state, rule=args.rule)
     out["workload"] = ("c4: 13B params, fp32 p/m/v (156 GB) in host memory, 130 subgroups of 100,000,000, "
                        "40 GB GPU budget, balanced plan re-derived per iteration; bf16 grads ~N(0,1e-3); 5 steps")
     if args.rule != "adamw":
@@ -555,6 +568,19 @@ def bench_c4(args, dos, torch, np):
     if out["n_subgroups_pinned"] < out["n_subgroups"]:
         out["workload"] += (f"; hipHostMalloc pins only {out['n_subgroups_pinned']} subgroups on this machine, the "
                             "others are in pageable host memory and are planned CPU-only")
+    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+        # The same state with the 16-bit parameters going through the pinned ring and the copy kernel: the
+        # configuration in which this host leaves something for the link to do, i.e. the staged, link-bound
+        # regime the interleaving is made for.
+        ring = run_interleaved(dos, torch, np, sizes, 40 * 10**9, steps=3, warmup=3, host_threads=args.host_threads,
+                               gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4 ring uploads", state=state,
+                               rule=args.rule, upload_flags=0)
+        out["with_ring_uploads"] = {k: ring[k] for k in (
+            "update_phase_s_per_iter", "best_s", "params_per_s", "ratio_to_lower_bound", "ratio_to_lower_bound_opt",
+            "h2d_GBps", "d2h_GBps", "h2d_frac_of_measured_link", "d2h_frac_of_measured_link", "gpu_fraction",
+            "uploads", "sample_mismatches_vs_oracle")}
+    state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
+    state.free()
     return out
 
 
