@@ -373,10 +373,13 @@ dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, vo
  * Elements past the last multiple of four are not touched. */
 dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream);
 
-/* Reads one byte of every 4 KiB page of a host buffer and writes it back, with
- * `threads` threads, so that the first host update of a buffer that so far was
- * only written by DMA, or never touched, does not pay for the page faults inside
- * the update phase.  Nobody else may write the buffer during the call. */
+/* Reads one byte of every 4 KiB page of a buffer and writes it back, with
+ * `threads` threads, so that the first host update of a host buffer that so far
+ * was only written by DMA, or never touched, does not pay for the page faults
+ * inside the update phase.  Also for device memory on a large-BAR machine (the
+ * 16-bit model that DOS_CTX_UPLOAD_DIRECT lets the host cores write): the first
+ * host access to a device page maps it, which costs about as much.  Nobody else
+ * may write the buffer during the call. */
 dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads);
 
 const char* dos_strerror(dos_status s);
