@@ -8,7 +8,10 @@
 // one kernel).  The kernel is bound by HBM bandwidth: ~0.5 flop per byte, no
 // reuse, so there is no LDS staging and no MFMA.  Every lane moves 16 bytes per
 // FP32 access; a wave's accesses are contiguous; a block owns a contiguous tile
-// so DRAM pages are opened once.
+// so DRAM pages are opened once.  The same launch exists for Adagrad and RMSProp
+// (Section 4.1 names them next to Adam): p and one accumulator, 20 bytes per
+// element.  The default launch is the untiled one (adam_kernel_tile /
+// accum_kernel_tile); the tiled layouts stay for launch-shape sweeps.
 //
 // Arithmetic: each operation is one IEEE binary32 operation (the file is built
 // with -ffp-contract=off, correctly rounded divide and square root, denormals

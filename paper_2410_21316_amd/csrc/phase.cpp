@@ -16,10 +16,12 @@
 //                 duplex.  Static residents (state already in device memory)
 //                 are updated in place, last.
 //   host lane  -- persistent worker threads take chunks of the CPU-planned
-//                 subgroups, run the host AdamW (which writes the 16-bit
-//                 parameters straight into a pinned ring: the paper's separate
-//                 downscale pass is fused away) and send each chunk to the
-//                 device model on a fourth stream.
+//                 subgroups and run the host update, which emits the 16-bit
+//                 parameters in the same pass (the paper's separate downscale
+//                 pass is fused away): straight into the device model through
+//                 the PCIe BAR where the device memory is host-mapped
+//                 (DOS_CTX_UPLOAD_DIRECT), else into a pinned ring from which
+//                 each chunk is sent to the device model on a fourth stream.
 //
 // The call joins both lanes before it returns.  Nothing is allocated here: slots,
 // ring, streams, events and threads belong to the context.
