@@ -353,6 +353,54 @@ def test_planner_prices_contention_and_falls_back_to_the_host_cores():
         dos.dos_plan_subgroups(dos.cost_model(56e9, 48e9, 230e9, 6e9, cpu_cost_per_dma_byte=-0.1), sizes, 4 * 10**9)
 
 
+@pytest.mark.parametrize("u0,beta,h2d,d2h,stages", [
+    (2.0e9, 0.004, 50e9, 45e9, True),      # slow host (the paper's regime): staging pays
+    (12.0e9, 0.035, 47e9, 45e9, True),     # fast host, mild contention: a small staged share pays
+    (16.0e9, 0.12, 40e9, 45e9, False),     # fast host whose stores share the link: staging costs more than it saves
+])
+def test_plan_observe_loop_converges_on_a_simulated_machine(u0, beta, h2d, d2h, stages):
+    """Closed loop, as a training run uses the library: plan, run a phase, observe, plan again -- on a
+    simulated machine with known rates, contention and 2 % timing noise.  The loop has to end within a few
+    percent of the best split for that machine (found by trying every count), whether that split stages
+    subgroups or keeps them all on the host cores."""
+    rng = random.Random(int(u0 / 1e6) + int(beta * 1e4))
+    sizes = [100_000_000] * 60
+    s_gpu = 230e9
+
+    def machine(n_gpu_sg, noise=True):
+        ng, nc = 1e8 * n_gpu_sg, 1e8 * (60 - n_gpu_sg)
+        jit = (lambda: 1.0 + rng.uniform(-0.02, 0.02)) if noise else (lambda: 1.0)
+        t_cpu = (nc + beta * 24.0 * ng) / u0 * jit()
+        t_h2d, t_d2h = (12 * ng + 2 * nc) / h2d * jit(), 12 * ng / d2h * jit()
+        t_gpu = max(t_h2d, t_d2h + 0.004, ng / s_gpu) if ng else 0.0
+        return ng, nc, t_cpu, t_gpu, t_h2d, t_d2h
+
+    best = min(max(machine(k, False)[2], machine(k, False)[3]) for k in range(61))
+    all_cpu = machine(0, False)[2]
+    cm = dos.cost_model(56e9, 48e9, s_gpu, 1.2 * u0)               # calibrated stand-alone: optimistic
+    walls = []
+    for it in range(14):
+        if it == 0:
+            k = 0                                                  # first phase on the host cores alone
+        else:
+            k = sum(dos.dos_plan_subgroups(cm, sizes, 40 * 10**9).targets)
+        ng, nc, t_cpu, t_gpu, t_h2d, t_d2h = machine(k)
+        st = dos.dos_phase_stats()
+        st.params_cpu, st.params_gpu = int(nc), int(ng)
+        st.h2d_bytes, st.d2h_bytes = 12.0 * ng + 2.0 * nc, 12.0 * ng
+        st.cpu_lane_s, st.gpu_lane_s = t_cpu, t_gpu
+        # the prefetches are busy for their own bytes' share of the direction's time
+        st.h2d_busy_s = t_h2d * (12.0 * ng) / (12.0 * ng + 2.0 * nc) if ng else -1.0
+        st.d2h_busy_s = t_d2h if ng else -1.0
+        dos.dos_cost_model_observe(cm, st)
+        walls.append((k, max(t_cpu, t_gpu)))
+    tail = walls[-4:]
+    assert all(w <= 1.06 * best for _, w in tail), (walls, best)
+    assert all((k > 0) == stages for k, _ in tail), walls
+    if stages:
+        assert max(w for _, w in tail) < all_cpu
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_balanced_plan_invariants_on_random_machines(seed):
     """Whatever the rates: the balanced plan is never worse (by its own estimate)
