@@ -132,6 +132,6 @@ const char* dos_strerror(dos_status s) {
 
 const char* dos_last_hip_error(void) { return dos::g_hip_error; }
 
-int32_t dos_version(void) { return 100; }
+int32_t dos_version(void) { return 110; }
 
 }  // extern "C"
