@@ -465,6 +465,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
              "h2d_GBps": st.h2d_bytes / st.wall_s / 1e9, "d2h_GBps": st.d2h_bytes / st.wall_s / 1e9,
              "h2d_busy_s": st.h2d_busy_s, "d2h_busy_s": st.d2h_busy_s, "gpu_busy_s": st.gpu_busy_s,
              "duplex_overlap_s": st.duplex_overlap_s, "cpu_lane_s": st.cpu_lane_s, "gpu_lane_s": st.gpu_lane_s,
+             "host_update_params_per_s": st.params_cpu / st.cpu_lane_s if st.cpu_lane_s > 0 else None,
              "lower_bound_s": lb_plan, "ratio_to_lower_bound": st.wall_s / lb_plan if lb_plan > 0 else None,
              "predicted_s": plan.c.predicted_s, "timed": step > warmup}
         results.append(r)
@@ -513,6 +514,7 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
            "h2d_GBps": best["h2d_GBps"], "d2h_GBps": best["d2h_GBps"],
            "h2d_frac_of_measured_link": best["h2d_GBps"] * 1e9 / link[0],
            "d2h_frac_of_measured_link": best["d2h_GBps"] * 1e9 / link[1],
+           "host_update_params_per_s": best["host_update_params_per_s"],
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
            "host_threads": host_threads, "uploads": {0: "pull", 2: "dma", 8: "direct"}[upload_flags],
            "sample_mismatches_vs_oracle": mism, "steps": results,
