@@ -81,12 +81,16 @@ def test_config3_seventy_subgroups_of_100m_sampled(hp):
     assert np.all(tail > 0)
 
 
-@pytest.mark.parametrize("heavy", [False, True])
-def test_interleaved_phase_on_100m_subgroups_sampled(heavy, hp):
+@pytest.mark.parametrize("heavy,direct", [(False, False), (True, False), (True, True)])
+def test_interleaved_phase_on_100m_subgroups_sampled(heavy, direct, hp):
     """Host-offloaded state in 100M-parameter subgroups run through
     dos_plan_subgroups + dos_run_update_phase exactly as bench.py does (3 slots of
     16 Mi parameters, all host cores, balanced plan), 3 steps; sampled oracle.
-    `heavy` uses the sweep's gradients: Student-t(3) x 1e-3 with 5 % exact zeros."""
+    `heavy` uses the sweep's gradients: Student-t(3) x 1e-3 with 5 % exact zeros; `direct` lets the host
+    workers store the 16-bit parameters straight into the device model (bench.py's default where the device
+    memory is mapped into the host's address space)."""
+    if direct and not dos.dos_device_large_bar(0):
+        pytest.skip("the device memory is not mapped into the host's address space")
     sizes = [100_000_000] * 10 + [37_000_003]           # a ragged last subgroup
     seed = S.BASE_SEED + (5 if heavy else 4)
     gkw = dict(heavy_tail=True, zero_pct=5.0) if heavy else {}
@@ -97,7 +101,8 @@ def test_interleaved_phase_on_100m_subgroups_sampled(heavy, hp):
     plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
     assert (plan.c.n_slots, plan.c.slot_params) == (3, 16 << 20)
     assert 0 < sum(plan.targets) < len(sizes)
-    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, threads)
+    ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, threads,
+                         flags=dos.DOS_CTX_UPLOAD_DIRECT if direct else 0)
     idxs = [torch.from_numpy(W.sample_index(n)) for n in sizes]
     want = [[state.hp[i][idxs[i]].numpy().copy(), np.zeros(idxs[i].numel(), np.float32),
              np.zeros(idxs[i].numel(), np.float32), np.zeros(idxs[i].numel(), np.uint16)] for i in range(len(sizes))]
