@@ -8,6 +8,9 @@
 // width) is bit-identical to the device result.
 #include <math.h>
 #include <string.h>
+#if defined(__x86_64__)
+#include <immintrin.h>
+#endif
 
 #include <thread>
 #include <vector>
@@ -127,6 +130,49 @@ void rmsprop_block(float* __restrict__ p, float* __restrict__ v, const uint16_t*
 }
 
 }  // namespace
+
+namespace {
+
+// Copies n 16-bit words from a small cache-resident buffer to memory that is written through the
+// PCIe BAR, with non-temporal 32-byte stores where the destination allows: each is one full posted
+// write instead of a cached store the core has to push out.
+#if defined(__x86_64__)
+__attribute__((target("avx2"))) void stream_copy_u16_avx2(uint16_t* dst, const uint16_t* src, uint64_t n) {
+  uint64_t i = 0;
+  while (i < n && ((uintptr_t)(dst + i) & 31u)) {  // head up to a 32-byte boundary
+    dst[i] = src[i];
+    ++i;
+  }
+  for (; i + 16 <= n; i += 16)
+    _mm256_stream_si256(reinterpret_cast<__m256i*>(dst + i),
+                        _mm256_loadu_si256(reinterpret_cast<const __m256i*>(src + i)));
+  for (; i < n; ++i) dst[i] = src[i];
+}
+#endif
+
+void stream_copy_u16(uint16_t* dst, const uint16_t* src, uint64_t n) {
+#if defined(__x86_64__)
+  static const bool avx2 = __builtin_cpu_supports("avx2");
+  if (avx2) {
+    stream_copy_u16_avx2(dst, src, n);
+    return;
+  }
+#endif
+  memcpy(dst, src, n * 2);
+}
+
+}  // namespace
+
+void host_adam_range_streamed(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp_dev, uint64_t n,
+                              const AdamScalars& s) {
+  constexpr uint64_t kBlock = 2048;  // 4 KiB of 16-bit output: stays in the first-level cache
+  alignas(64) uint16_t tmp[kBlock];
+  for (uint64_t off = 0; off < n; off += kBlock) {
+    const uint64_t cnt = n - off < kBlock ? n - off : kBlock;
+    host_adam_range(p + off, m ? m + off : nullptr, v + off, g + off, tmp, cnt, s);
+    stream_copy_u16(p_lp_dev + off, tmp, cnt);
+  }
+}
 
 void store_fence() {
 #if defined(__x86_64__) || defined(__i386__)

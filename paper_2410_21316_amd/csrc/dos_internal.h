@@ -49,6 +49,12 @@ dos_status launch_probe_traffic(const dos_subgroup* sg, int mode, int lds_bytes,
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,
                      const AdamScalars& s);
 
+// The same update with the 16-bit output going to memory the host writes through the PCIe BAR
+// (device memory): the output of each small block is formed in a cache-resident buffer and sent
+// with non-temporal stores.
+void host_adam_range_streamed(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp_dev, uint64_t n,
+                              const AdamScalars& s);
+
 // Drains the calling core's write-combining buffers (x86 sfence).
 void store_fence();
 

@@ -194,8 +194,8 @@ void worker_main(dos_ctx* c, int tid) {
         // core writes through the PCIe BAR (posted writes, combined into whole lines on the way)
         const auto td0 = clk::now();
         uint16_t* dst = sg.p_lp + ch.off;
-        dos::host_adam_range(sg.p + ch.off, sg.m ? sg.m + ch.off : nullptr, sg.v + ch.off, sg.g + ch.off, dst,
-                             ch.cnt, c->job_scalars);
+        dos::host_adam_range_streamed(sg.p + ch.off, sg.m ? sg.m + ch.off : nullptr, sg.v + ch.off, sg.g + ch.off,
+                                      dst, ch.cnt, c->job_scalars);
         last_direct = dst + (ch.cnt - 1);
         lt.compute += secs(td0, clk::now());
         continue;
