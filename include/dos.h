@@ -373,6 +373,13 @@ dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, vo
  * Elements past the last multiple of four are not touched. */
 dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream);
 
+/* Asks the kernel to back a range of ordinary (pageable) host memory with huge
+ * pages where it can (Linux madvise MADV_HUGEPAGE on the whole pages inside the
+ * range; a no-op elsewhere).  Call it before the memory is first touched: the host
+ * update streams through four arrays, and with 2 MiB pages the hardware
+ * prefetchers are not stopped every 4 KiB.  DOS_ESTATE if the kernel refuses. */
+dos_status dos_host_advise_hugepages(void* ptr, uint64_t bytes);
+
 /* Reads one byte of every 4 KiB page of a buffer and writes it back, with
  * `threads` threads, so that the first host update of a host buffer that so far
  * was only written by DMA, or never touched, does not pay for the page faults

@@ -100,6 +100,7 @@ SIGNATURES = {
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
     "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "dos_probe_adam_traffic": (C.c_int, [C.POINTER(dos_subgroup), C.c_int32, C.c_int32, C.c_void_p]),
+    "dos_host_advise_hugepages": (C.c_int, [C.c_void_p, C.c_uint64]),
     "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
     "dos_last_hip_error": (C.c_char_p, []),
@@ -284,6 +285,11 @@ def dos_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
 def dos_probe_adam_traffic(sg: dos_subgroup, mode: int, stream: int = 0, lds_bytes: int = 0) -> None:
     check(load().dos_probe_adam_traffic(C.byref(sg), int(mode), int(lds_bytes), C.c_void_p(stream)),
           "dos_probe_adam_traffic")
+
+
+def dos_host_advise_hugepages(ptr: int, nbytes: int) -> bool:
+    """True when the kernel accepted the advice."""
+    return load().dos_host_advise_hugepages(C.c_void_p(ptr), int(nbytes)) == DOS_OK
 
 
 def dos_host_prefault(ptr: int, nbytes: int, threads: int = 1) -> None:

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime_api.h>
 #include <stdio.h>
 #include <string.h>
+#if defined(__linux__)
+#include <sys/mman.h>
+#endif
 
 #include <atomic>
 #include <thread>
@@ -90,6 +93,17 @@ dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t 
   if (sg->n == 0) return DOS_OK;
   if (sg->state_loc != DOS_DEVICE || sg->grad_loc != DOS_DEVICE) return DOS_ESTATE;
   return dos::launch_probe_traffic(sg, mode, lds_bytes, hip_stream);
+}
+
+dos_status dos_host_advise_hugepages(void* ptr, uint64_t bytes) {
+  if (!ptr && bytes) return DOS_EINVAL;
+#if defined(__linux__) && defined(MADV_HUGEPAGE)
+  const uintptr_t page = 4096;
+  const uintptr_t lo = ((uintptr_t)ptr + page - 1) & ~(page - 1);
+  const uintptr_t hi = ((uintptr_t)ptr + bytes) & ~(page - 1);
+  if (hi > lo && madvise(reinterpret_cast<void*>(lo), hi - lo, MADV_HUGEPAGE) != 0) return DOS_ESTATE;
+#endif
+  return DOS_OK;
 }
 
 dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {

@@ -77,7 +77,7 @@ class OffloadedState:
     state to the device, following the plan as Section 4.1 describes."""
 
     def __init__(self, sizes, seed=S.BASE_SEED, device="cuda:0", fill=True, pinned_reserve_bytes=0,
-                 pageable_rest=False, pin_at_most=None):
+                 pageable_rest=False, pin_at_most=None, hugepages=True):
         """If the machine cannot pin all of it (leaving `pinned_reserve_bytes` for
         the caller's own pinned buffers), the subgroups that do not fit either
         live in ordinary pageable host memory (`pageable_rest=True`: they can then
@@ -121,11 +121,15 @@ class OffloadedState:
                 self.hg.append(blk.tensor(torch.bfloat16, 3 * fb, n))
             else:                                     # ordinary host memory, 64-byte aligned by torch
                 self.hp.append(torch.empty(n, dtype=torch.float32))
-                self.hm.append(torch.zeros(n, dtype=torch.float32))
-                self.hv.append(torch.zeros(n, dtype=torch.float32))
+                self.hm.append(torch.empty(n, dtype=torch.float32))
+                self.hv.append(torch.empty(n, dtype=torch.float32))
                 self.hg.append(torch.empty(n, dtype=torch.bfloat16))
                 for t in (self.hp[i], self.hm[i], self.hv[i], self.hg[i]):
+                    if hugepages:                     # before the first touch
+                        dos.dos_host_advise_hugepages(t.data_ptr(), t.numel() * t.element_size())
                     dos.dos_host_prefault(t.data_ptr(), t.numel() * t.element_size(), 16)
+                self.hm[i].zero_()
+                self.hv[i].zero_()
             if fill:
                 S.fill_chunked(lambda start, count: S.params(seed, i, start, count, device), tmp[:n])
                 self.hp[i].copy_(tmp[:n])
