@@ -5,11 +5,15 @@ One JSON line on stdout.  Primary workload (`value`): the device-resident AdamW
 update over a GPT-2-small-sized flat partition, 4 subgroups of 31,000,000
 parameters (fp32 p/m/v, bf16 gradients with 1 % exact zeros, bf16 parameter copy
 out); a step is one pass over all four subgroups through dos_adam_step.  Extra
-workloads ride in the same line under "extra": the 7B-parameter resident state
-(70 x 100M) and the 13B-parameter host-offloaded state (130 x 100M, 40 GB GPU
-budget) run through dos_plan_subgroups + dos_run_update_phase.
+workloads ride in the same line under "extra": the single 1Mi-parameter subgroup,
+the 7B-parameter resident state (70 x 100M), the 13B-parameter host-offloaded
+state (130 x 100M, 40 GB GPU budget) run through dos_plan_subgroups +
+dos_run_update_phase (with the host lane's 16-bit output stored straight into
+device memory where the machine allows, and once more through the pinned ring),
+and Adagrad / RMSProp on the primary workload's shape.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,rules|none] [--ablation] [--sweep] [--full-size]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,rules|none] [--upload auto|direct|pull|dma]
+                    [--rule adamw|adagrad|rmsprop] [--host-threads T] [--ablation] [--sweep] [--full-size] [--ceilings]
 """
 from __future__ import annotations
 
