@@ -826,7 +826,7 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     float* v = m + n;
     uint16_t* g = (uint16_t*)(v + n);
     uint16_t* lp = g + n;
-    dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f};
+    dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f, DOS_OPT_ADAMW};
     const int kreps = 5;
     dos_status k = dos::launch_adam(p, m, v, g, lp, n, sc, c->comp, nullptr);  // warm-up
     hipError_t he = hipEventRecord(ev[0], c->comp);
