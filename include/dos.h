@@ -118,8 +118,11 @@ typedef struct dos_launch_cfg {
  * allocation, no synchronisation, so a stream under HIP graph capture records
  * just the kernel launch (the per-step scalars are kernel arguments: a replay
  * repeats the captured step number).  HBM traffic is 28 bytes per element (reads
- * 4+4+4+2, writes 4+4+4+2; 20 bytes for the rules without a first moment).  Errors: DOS_EINVAL (NULL, bad hyper-parameters,
- * state_loc/grad_loc not DOS_DEVICE is DOS_ESTATE), DOS_EALIGN, DOS_EHIP. */
+ * 4+4+4+2, writes 4+4+4+2; 20 bytes for the rules without a first moment).
+ * n may exceed 2^32 (arrays are addressed with 64-bit offsets); the limit is
+ * 2^31 - 1 tiles of 256 elements, far beyond what device memory holds.
+ * Errors: DOS_EINVAL (NULL, bad hyper-parameters, n beyond that limit),
+ * DOS_ESTATE (state_loc or grad_loc not DOS_DEVICE), DOS_EALIGN, DOS_EHIP. */
 dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);
 
 /* Same, with an explicit launch shape.  The low four bits of `variant` pick the

@@ -452,7 +452,10 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   uint64_t n_tiles = (units + tile - 1) / tile;
   if (n_tiles == 0) n_tiles = 1;  // tail only
   if (blocks == 0 || (uint64_t)blocks > n_tiles) blocks = (int64_t)n_tiles;
-  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;  // grid-stride covers the rest
+  if (blocks > 0x7FFFFFFF) {
+    if (layout == 4) return DOS_EINVAL;  // one block per tile: more tiles than a grid can hold
+    blocks = 0x7FFFFFFF;                 // grid-stride covers the rest
+  }
   // XCD-grouped tile order (untiled AdamW layout only): the grid becomes a multiple of 8 << k
   uint32_t xcd_shift = 32;
   if (cfg && cfg->xcd_group) {
