@@ -6,19 +6,29 @@ Three pieces:
 * ``stride_k``      -- the closed form of the performance model (Section 4.2, Eq. 1).
 * ``stride_targets`` / ``run_update_trace`` -- the placement rule and the action
   order of the scheduling algorithm (Section 4.3, Algorithm 1).
-* ``phase_cost`` / ``brute_force_plan`` -- this build's own makespan estimate for
-  an arbitrary CPU/GPU assignment and its exhaustive minimiser, used to bound
-  the gap of the library's "balanced" planner.  The estimate is not from the
-  paper; it extends the same balance (host update time vs. link time vs. GPU
-  time) to unequal subgroup sizes, separate link rates per direction and a
-  fused host downscale.
+* ``phase_cost`` / ``brute_force_plan`` -- a makespan estimate for an arbitrary
+  CPU/GPU assignment and its exhaustive minimiser, used to bound the gap of the
+  library's "balanced" planner.  The estimate is this build's own reading of the
+  performance model, not a formula the paper prints: it keeps Eq. 1's terms
+  (3S/B per staged subgroup and direction, S/(2B) per CPU-updated subgroup,
+  S/U_g, S/U_c) and writes them per lane instead of per stride period, so that
+  unequal subgroup sizes, separate link rates per direction, a fused host
+  downscale, static residents (Section 4.1), slots smaller than a subgroup,
+  the two-array update rules and the contention between the lanes that
+  Section 5.4 reports can be priced.
 
 Pins (tests/test_plan_pins.py): the paper's second-machine worked example
 (Section 5.4: B=3, U_g=35, U_c=2, D_c=8.7 G params/s gives stride 2), "k=2 means
 every alternate subgroup" (Sections 5.3, 5.4), the 8-subgroup timeline of the
 update figure (33 % on the GPU, two static residents placed last; Section 4.1),
 independence of k from the subgroup size (Section 4.2), and the balance identity
-of Eq. 1 itself.
+of Eq. 1 itself.  ``phase_cost``: every branch against numbers worked out by
+hand from the terms above, the balance of Eq. 1 recovered from it (at the
+paper's k both lanes end together), and an event-by-event timeline of the
+three-stage pipeline that brackets the closed form.  The rounding of k is a
+reading (the paper's one example fits rounding down and to nearest alike) and
+is pinned as such.  tests/test_oracle_mutants.py plants mistakes in this file,
+each caught by a pin.
 """
 from __future__ import annotations
 
@@ -88,29 +98,48 @@ def run_update_trace(n_sg: int, k: int, residents: Iterable[int] = ()) -> List[T
 
 def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d2h_Bps: float,
                gpu_params_per_s: float, cpu_params_per_s: float, launch_overhead_s: float,
-               n_slots: int, resident: Sequence[int] = (), slot_params: int = 0) -> Tuple[float, float]:
+               n_slots: int, resident: Sequence[int] = (), slot_params: int = 0,
+               fp32_arrays: int = 3, cpu_cost_per_dma_byte: float = 0.0) -> Tuple[float, float]:
     """(predicted_s, lower_bound_s) of one update phase.
 
-    CPU-planned subgroups cost n/U_c on the host and 2 bytes/param of H2D for the
-    refreshed 16-bit parameters; GPU-planned ones cost 12 bytes/param each way
-    (p, m, v in FP32) and n/U_g + launch on the GPU.  With two or more staging
-    slots the three lanes overlap and only the first prefetch and its kernel are
-    exposed in front of the D2H lane (the first piece, when subgroups are staged in
-    pieces of ``slot_params``); with a single slot prefetch, kernel and
-    flush of every GPU subgroup run back to back.  Static residents (indices in
-    ``resident``, all GPU-planned) never cross the link: they only add GPU time."""
+    The terms are those of the performance model (Section 4.2), written per lane
+    instead of per stride period.  With A = ``fp32_arrays`` FP32 state arrays
+    (3 for Adam: p, m, v -- the "3" of Eq. 1; 2 for the rules that keep p and one
+    accumulator), a GPU-planned subgroup of n parameters moves 4*A*n bytes each
+    way (Eq. 1's 3S/B) and costs n/U_g + one launch on the GPU; a CPU-planned one
+    costs n/U_c on the host and 2n bytes of H2D for its refreshed 16-bit
+    parameters (Eq. 1's S/(2B)).  Static residents (indices in ``resident``, all
+    GPU-planned) never cross the link: they only add GPU time (Section 4.1).
+
+    GPU lane.  With two or more staging slots prefetch, kernel and flush of
+    consecutive pieces overlap, so the lane takes as long as its slowest stage:
+    all H2D traffic, or all kernels, or the D2H traffic behind the lead of the
+    first piece (its prefetch and its kernel; a piece is a whole subgroup, or
+    ``slot_params`` parameters when subgroups stream through smaller slots).  With
+    a single slot prefetch, kernel and flush of every staged subgroup run back to
+    back, next to the 16-bit uploads.
+
+    Host lane.  Both lanes share the host's memory system (Section 5.4, CPU cores
+    per GPU): every staged byte, in either direction, takes
+    ``cpu_cost_per_dma_byte`` parameters of update work away from the host cores,
+    so the host lane takes (N_C + cost * 2 * 4*A*N_G) / U_c.
+
+    predicted = max(host lane, GPU lane); lower = max(link time per direction)."""
     assert len(sizes) == len(target)
+    assert fp32_arrays in (2, 3)
     R = set(resident)
     assert all(target[i] == ON_GPU for i in R)
     n_g = [n for i, (n, t) in enumerate(zip(sizes, target)) if t == ON_GPU and i not in R]
     n_r = [sizes[i] for i in R]
     n_c = [n for n, t in zip(sizes, target) if t == ON_CPU]
     N_G, N_C, N_R = float(sum(n_g)), float(sum(n_c)), float(sum(n_r))
-    h2d_bytes = 12.0 * N_G + 2.0 * N_C
-    d2h_bytes = 12.0 * N_G
+    state_bytes = 4.0 * fp32_arrays
+    h2d_bytes = state_bytes * N_G + 2.0 * N_C
+    d2h_bytes = state_bytes * N_G
     t_h2d = h2d_bytes / h2d_Bps
     t_d2h = d2h_bytes / d2h_Bps
-    t_cpu = N_C / cpu_params_per_s
+    staged_bytes = 2.0 * state_bytes * N_G
+    t_cpu = (N_C + cpu_cost_per_dma_byte * staged_bytes) / cpu_params_per_s
     t_gpu = (N_G + N_R) / gpu_params_per_s + launch_overhead_s * (len(n_g) + len(n_r))
     if not n_g:
         lane = max(t_h2d, t_gpu)
@@ -118,10 +147,10 @@ def phase_cost(sizes: Sequence[int], target: Sequence[int], *, h2d_Bps: float, d
         first = n_g[0]
         if slot_params:                      # subgroups stream through the slots in pieces
             first = min(first, slot_params)
-        lead = 12.0 * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s
+        lead = state_bytes * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s
         lane = max(t_h2d, lead + t_d2h, t_gpu)
     else:
-        lane = 12.0 * N_G / h2d_Bps + t_gpu + t_d2h
+        lane = state_bytes * N_G / h2d_Bps + t_gpu + t_d2h
         lane = max(lane, t_h2d)
     predicted = max(t_cpu, lane)
     lower = max(t_h2d, t_d2h)

@@ -143,3 +143,105 @@ def test_planted_mistake_is_caught(name, edits, tmp_path, monkeypatch):
 def test_unmodified_reference_passes_every_pin():
     for check in PIN_CHECKS:
         check()
+
+
+# ---- the planner reference (oracle/plan_ref.py) -----------------------------------------------------
+
+import importlib.util
+
+import test_plan_pins as plan_pins
+
+PLAN_SRC = os.path.join(os.path.dirname(SRC), "plan_ref.py")
+
+PLAN_PIN_CHECKS = [
+    plan_pins.test_second_machine_worked_example,
+    plan_pins.test_eq1_balances_host_time_against_link_plus_gpu_time,
+    plan_pins.test_faster_host_means_larger_stride_and_faster_link_smaller,
+    plan_pins.test_stride_rounding_follows_the_reading_taken,
+    plan_pins.test_stride_two_is_every_alternate_subgroup,
+    plan_pins.test_update_figure_timeline,
+    plan_pins.test_every_subgroup_is_updated_exactly_once,
+    plan_pins.test_cost_function_limits,
+    plan_pins.test_brute_force_beats_both_extremes,
+    plan_pins.test_overlapped_lane_waits_for_the_flushes_behind_the_first_piece,
+    plan_pins.test_pieces_shorten_the_lead,
+    plan_pins.test_single_slot_serialises_the_staged_subgroups_next_to_the_uploads,
+    plan_pins.test_residents_cost_gpu_time_only,
+    plan_pins.test_two_array_rules_move_eight_bytes_per_parameter,
+    plan_pins.test_staged_traffic_is_charged_to_the_host_lane,
+    plan_pins.test_eq1_balance_is_the_models_balance,
+    lambda: plan_pins.test_lane_estimate_against_an_event_by_event_timeline(60e9, 40e9, 200e9, 3),
+    lambda: plan_pins.test_lane_estimate_against_an_event_by_event_timeline(40e9, 60e9, 200e9, 2),
+    lambda: plan_pins.test_lane_estimate_against_an_event_by_event_timeline(50e9, 50e9, 2e9, 3),
+    lambda: plan_pins.test_lane_estimate_against_an_event_by_event_timeline(55e9, 48e9, 230e9, 1),
+]
+
+PLAN_MUTANTS = [
+    ("Eq. 1: link term counted once instead of three times", [("(3.0 / B + 1.0 / U_g)", "(1.0 / B + 1.0 / U_g)")]),
+    ("Eq. 1: upload term added instead of subtracted", [("return (3.0 / B + 1.0 / U_g) / (1.0 / U_c + 1.0 / D_c - 1.0 / (2.0 * B))",
+                                                         "return (3.0 / B + 1.0 / U_g) / (1.0 / U_c + 1.0 / D_c + 1.0 / (2.0 * B))")]),
+    ("Eq. 1: downscale term dropped", [("return (3.0 / B + 1.0 / U_g) / (1.0 / U_c + 1.0 / D_c - 1.0 / (2.0 * B))",
+                                        "return (3.0 / B + 1.0 / U_g) / (1.0 / U_c - 1.0 / (2.0 * B))")]),
+    ("Eq. 1: GPU term dropped", [("(3.0 / B + 1.0 / U_g)", "(3.0 / B)")]),
+    ("stride rounds down", [("return max(1, int(k + 0.5))", "return max(1, int(k))")]),
+    ("stride rounds up", [("return max(1, int(k + 0.5))", "return max(1, int(k + 0.999))")]),
+    ("stride test off by one", [("(k >= 1 and (i + 1) % k == 0)) else ON_CPU", "(k >= 1 and i % k == 0)) else ON_CPU")]),
+    ("residents ignored by the placement", [("[ON_GPU if (i in R or (k >= 1", "[ON_GPU if ((k >= 1")]),
+    ("trace: flush and prefetch swapped", [('trace.append(("flush_out", prev[0]))', 'trace.append(("prefetch_in", prev[0]))'),
+                                           ('trace.append(("prefetch_in", nxt[0]))', 'trace.append(("flush_out", nxt[0]))')]),
+    ("trace: prefetch looks backwards", [("nxt = [j for j in range(i + 1, n_sg)", "nxt = [j for j in range(i - 1, -1, -1)")]),
+    ("trace: downscale queue not handed over", [('trace.append(("cpu_downscale", list(queue)))', 'trace.append(("cpu_downscale", []))')]),
+    ("cost: flushes priced at the prefetch rate in the overlapped lane", [("lane = max(t_h2d, lead + t_d2h, t_gpu)",
+                                                                           "lane = max(t_h2d, lead + t_h2d, t_gpu)")]),
+    ("cost: lead of the first piece dropped", [("lane = max(t_h2d, lead + t_d2h, t_gpu)", "lane = max(t_h2d, t_d2h, t_gpu)")]),
+    ("cost: lead priced at the flush rate", [("lead = state_bytes * first / h2d_Bps", "lead = state_bytes * first / d2h_Bps")]),
+    ("cost: lead without its kernel", [("lead = state_bytes * first / h2d_Bps + first / gpu_params_per_s + launch_overhead_s",
+                                        "lead = state_bytes * first / h2d_Bps")]),
+    ("cost: slot size ignored", [("first = min(first, slot_params)", "first = first")]),
+    ("cost: the largest staged subgroup leads", [("first = n_g[0]", "first = max(n_g)")]),
+    ("cost: residents dropped from the GPU time", [("t_gpu = (N_G + N_R) / gpu_params_per_s + launch_overhead_s * (len(n_g) + len(n_r))",
+                                                    "t_gpu = N_G / gpu_params_per_s + launch_overhead_s * len(n_g)")]),
+    ("cost: residents cross the link", [("h2d_bytes = state_bytes * N_G + 2.0 * N_C", "h2d_bytes = state_bytes * (N_G + N_R) + 2.0 * N_C"),
+                                        ("d2h_bytes = state_bytes * N_G", "d2h_bytes = state_bytes * (N_G + N_R)")]),
+    ("cost: residents-only lane forgets the kernels", [("lane = max(t_h2d, t_gpu)\n    elif", "lane = t_h2d\n    elif")]),
+    ("cost: uploads dropped from H2D", [("h2d_bytes = state_bytes * N_G + 2.0 * N_C", "h2d_bytes = state_bytes * N_G")]),
+    ("cost: uploads priced at four bytes", [("h2d_bytes = state_bytes * N_G + 2.0 * N_C", "h2d_bytes = state_bytes * N_G + 4.0 * N_C")]),
+    ("cost: three arrays whatever the rule", [("state_bytes = 4.0 * fp32_arrays", "state_bytes = 12.0")]),
+    ("cost: contention charged for one direction only", [("staged_bytes = 2.0 * state_bytes * N_G", "staged_bytes = state_bytes * N_G")]),
+    ("cost: contention term dropped", [("t_cpu = (N_C + cpu_cost_per_dma_byte * staged_bytes) / cpu_params_per_s",
+                                        "t_cpu = N_C / cpu_params_per_s")]),
+    ("cost: contention charged for the uploads too", [("staged_bytes = 2.0 * state_bytes * N_G", "staged_bytes = 2.0 * state_bytes * N_G + 2.0 * N_C")]),
+    ("cost: single slot overlaps the flushes", [("lane = state_bytes * N_G / h2d_Bps + t_gpu + t_d2h", "lane = state_bytes * N_G / h2d_Bps + t_gpu")]),
+    ("cost: single slot forgets the uploads", [("        lane = max(lane, t_h2d)\n", "")]),
+    ("cost: launches not counted", [("launch_overhead_s * (len(n_g) + len(n_r))", "0.0")]),
+    ("cost: host lane not part of the makespan", [("predicted = max(t_cpu, lane)", "predicted = lane")]),
+    ("cost: lower bound prices one direction", [("lower = max(t_h2d, t_d2h)", "lower = t_h2d")]),
+    ("brute force keeps the worst", [("if best is None or c < best:", "if best is None or c > best:")]),
+]
+
+
+@pytest.mark.parametrize("name,edits", PLAN_MUTANTS, ids=[m[0] for m in PLAN_MUTANTS])
+def test_planted_mistake_in_the_planner_reference_is_caught(name, edits, tmp_path, monkeypatch):
+    text = open(PLAN_SRC).read()
+    for old, new in edits:
+        assert text.count(old) >= 1, f"reference text changed: {old!r}"
+        text = text.replace(old, new, 1)
+    py = tmp_path / "plan_ref_mutant.py"
+    py.write_text(text)
+    spec = importlib.util.spec_from_file_location("plan_ref_mutant", str(py))
+    mutant = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mutant)
+    monkeypatch.setattr(plan_pins, "ref", mutant)
+    failed = False
+    for check in PLAN_PIN_CHECKS:
+        try:
+            check()
+        except AssertionError:
+            failed = True
+            break
+    assert failed, f"no pin noticed: {name}"
+
+
+def test_unmodified_planner_reference_passes_every_pin():
+    for check in PLAN_PIN_CHECKS:
+        check()

@@ -71,10 +71,15 @@ COST = dict(h2d_Bps=55e9, d2h_Bps=48e9, gpu_params_per_s=190e9, cpu_params_per_s
 
 
 def test_cost_function_matches_reference():
+    """dos_plan_cost against the reference's estimate for random assignments, slot counts, piece sizes,
+    residents, both state widths (three arrays for AdamW, two for Adagrad / RMSProp) and with and without
+    the charge for what staged traffic takes away from the host lane."""
     rng = random.Random(7)
-    cm = dos.cost_model(COST["h2d_Bps"], COST["d2h_Bps"], COST["gpu_params_per_s"], COST["cpu_params_per_s"], 0.0,
-                        COST["launch_overhead_s"])
-    for _ in range(200):
+    for _ in range(400):
+        arrays = rng.choice([3, 3, 2])
+        contention = rng.choice([0.0, 0.0, 0.01, 0.04, 0.11])
+        cm = dos.cost_model(COST["h2d_Bps"], COST["d2h_Bps"], COST["gpu_params_per_s"], COST["cpu_params_per_s"], 0.0,
+                            COST["launch_overhead_s"], fp32_arrays=arrays, cpu_cost_per_dma_byte=contention)
         n = rng.randint(1, 14)
         sizes = [rng.randint(1, 400) * 1_000_000 for _ in range(n)]
         tgt = [rng.randint(0, 1) for _ in range(n)]
@@ -87,9 +92,29 @@ def test_cost_function_matches_reference():
         sp = rng.choice([0, 16 << 20])
         got = dos.dos_plan_cost(cm, sizes, tgt, slots, res, sp)
         want = ref.phase_cost(sizes, tgt, n_slots=slots, resident=[i for i in range(n) if res[i]], slot_params=sp,
-                              **COST)
+                              fp32_arrays=arrays, cpu_cost_per_dma_byte=contention, **COST)
         assert got[0] == pytest.approx(want[0], rel=1e-12)
         assert got[1] == pytest.approx(want[1], rel=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_balanced_mode_with_contention_and_two_arrays_finds_the_brute_force_optimum(seed):
+    """The same exhaustive check with the two product terms the first one leaves at their defaults."""
+    rng = random.Random(1000 + seed)
+    n = rng.randint(4, 11)
+    sizes = [rng.randint(40, 160) * 1_000_000 for _ in range(n)]
+    cost = dict(COST)
+    cost["cpu_params_per_s"] = rng.choice([1e9, 3e9, 7e9, 14e9])
+    extra = dict(fp32_arrays=rng.choice([2, 3]), cpu_cost_per_dma_byte=rng.choice([0.0, 0.01, 0.03, 0.06]))
+    cm = dos.cost_model(cost["h2d_Bps"], cost["d2h_Bps"], cost["gpu_params_per_s"], cost["cpu_params_per_s"], 0.0,
+                        cost["launch_overhead_s"], **extra)
+    plan = dos.dos_plan_subgroups(cm, sizes, 40 * 10**9, dos.DOS_PLAN_BALANCED)
+    best, _ = ref.brute_force_plan(sizes, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost, **extra)
+    mine, low = ref.phase_cost(sizes, plan.targets, n_slots=plan.c.n_slots, slot_params=plan.c.slot_params, **cost,
+                               **extra)
+    assert plan.c.predicted_s == pytest.approx(mine, rel=1e-12)
+    assert plan.c.lower_bound_s == pytest.approx(low, rel=1e-12)
+    assert mine <= best * (1 + 1e-12)
 
 
 @pytest.mark.parametrize("seed", range(12))
