@@ -136,8 +136,9 @@ def bench_c2(args, dos, torch, np):
         # known-size copy kernel for scaling the profiler's traffic counters: 1 GiB read + 1 GiB written
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
         b = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+        from paper_2410_21316_amd import probe
         for _ in range(3):
-            dos.dos_probe_copy(a.data_ptr(), b.data_ptr(), 1 << 30, stream.cuda_stream)
+            probe.dos_probe_copy(a.data_ptr(), b.data_ptr(), 1 << 30, stream.cuda_stream)
         stream.synchronize()
         del a, b
     wall, ev_s, launches = timed_resident(state, dos, torch, hp_kw, args.steps, args.warmup, stream)
@@ -236,7 +237,7 @@ def bench_other_rules(args, dos, torch, np):
 def bench_ceilings(args, dos, torch, np):
     """What bounds the AdamW kernel: its own launch with only the loads, only the stores, both without the
     arithmetic, and the full kernel, on 4 x 100M-parameter subgroups (rotated, so nothing is reused from a cache)."""
-    from paper_2410_21316_amd import workloads as W
+    from paper_2410_21316_amd import probe, workloads as W
     import dos_synth as S
     n = 100_000_000
     state = W.ResidentState([n] * 4, S.BASE_SEED + 7, "cuda:0")
@@ -263,13 +264,13 @@ def bench_ceilings(args, dos, torch, np):
                    "'capped' = its cap on resident waves per compute unit, 'uncapped' = none"}
     out["adamw_capped_GBps"] = rate(lambda sg: dos.dos_adam_step(sg, hp, sh), 28)
     out["adamw_uncapped_GBps"] = rate(lambda sg: dos.dos_adam_step_cfg(sg, hp, sh, variant=0x74, lds_bytes=-1), 28)
-    for name, lds in (("capped", 0), ("uncapped", -1)):
-        rd = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 0, sh, lds), 14)
-        both = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 2, sh, lds), 28)
+    for name, lds in (("capped", probe.DEFAULT_LDS_CAP), ("uncapped", 0)):
+        rd = rate(lambda sg: probe.dos_probe_adam_traffic(sg, 0, sh, lds), 14)
+        both = rate(lambda sg: probe.dos_probe_adam_traffic(sg, 2, sh, lds), 28)
         out[f"loads_only_{name}_GBps"] = rd
         out[f"loads_and_stores_no_math_{name}_GBps"] = both
-    for name, lds in (("capped", 0), ("uncapped", -1)):              # last: these zero the state
-        out[f"stores_only_{name}_GBps"] = rate(lambda sg: dos.dos_probe_adam_traffic(sg, 1, sh, lds), 14)
+    for name, lds in (("capped", probe.DEFAULT_LDS_CAP), ("uncapped", 0)):   # last: these zero the state
+        out[f"stores_only_{name}_GBps"] = rate(lambda sg: probe.dos_probe_adam_traffic(sg, 1, sh, lds), 14)
     rd = max(out["loads_only_capped_GBps"], out["loads_only_uncapped_GBps"])
     wr = max(out["stores_only_capped_GBps"], out["stores_only_uncapped_GBps"])
     out["time_shared_mix_GBps"] = 1.0 / (0.5 / rd + 0.5 / wr)

@@ -3,13 +3,16 @@
  * (arXiv 2410.21316) for one AMD MI355X (gfx950) GPU and its host cores.
  *
  * Plain C ABI: raw pointers (each documented as host or device), sizes and
- * status codes.  No function throws, aborts or prints.  Unless stated
- * otherwise, validation precedes work: when a call returns an error no element
- * of any caller array has been modified.  The library never allocates or pins
- * memory inside dos_adam_step / dos_adam_step_host / dos_run_update_phase
- * (Section 4.1: interleaving must not incur allocation costs; all host buffers
- * are pre-allocated and pre-pinned) -- staging memory and streams are handed in
- * at context creation.
+ * status codes.  No function prints or aborts, and none lets a C++ exception
+ * cross the boundary: where host memory or a thread cannot be had the call
+ * returns DOS_ENOMEM.  Unless stated otherwise, validation precedes work: when a
+ * call returns an error no element of any caller array has been modified.  The
+ * library never allocates or pins memory inside dos_adam_step or
+ * dos_run_update_phase, host memory included (Section 4.1: interleaving must not
+ * incur allocation costs; all host buffers are pre-allocated and pre-pinned) --
+ * staging memory and streams are handed in at context creation, and the work
+ * lists and statistics buffers of a phase are sized then.  dos_adam_step_host
+ * allocates nothing but its threads.
  *
  * The update (Sections 1, 2 "mixed precision", 4.1: FP32 parameters, momentum
  * and variance; 16-bit gradients in, 16-bit parameter copy out; Adam).  The
@@ -45,7 +48,8 @@ typedef enum dos_status {
   DOS_EALIGN = -2,  /* an array is not 16-byte aligned                               */
   DOS_EBUDGET = -3, /* GPU budget / staging memory too small for one slot            */
   DOS_EHIP = -4,    /* a HIP call failed (sticky in a context)                       */
-  DOS_ESTATE = -5   /* memory location and requested target do not fit together      */
+  DOS_ESTATE = -5,  /* memory location and requested target do not fit together      */
+  DOS_ENOMEM = -6   /* host memory or a thread could not be obtained                 */
 } dos_status;
 
 typedef enum dos_loc {
@@ -284,15 +288,21 @@ typedef struct dos_phase_stats {
                                      time a direction sat idle between its copies    */
 } dos_phase_stats;
 
-/* Creates a context: events, worker threads, the prefetch thread of the GPU lane
- * and (unless given) streams.  slot_mem
+/* Creates a context: everything a phase needs besides the caller's memory is
+ * made here, once, so that the phases themselves allocate nothing (Section 4.1:
+ * the buffers of the interleaved update are pre-allocated and pre-pinned, because
+ * allocation inside the update would cost more than the overlap gains) -- events,
+ * worker threads, the prefetch thread of the GPU lane, the lists of pieces and
+ * chunks (a phase may have up to 16384 staged pieces and 65536 host chunks; one
+ * that needs more is refused with DOS_EBUDGET), the statistics buffers and
+ * (unless given) streams.  slot_mem
  * and pinned_stage stay owned by the caller and must outlive the context.  A
  * context runs one phase at a time; contexts that use the library's own streams
  * on the same device share them, so their phases should not overlap either.
  * Errors: DOS_EINVAL (NULL, host_threads < 1, slot_params not a multiple of 64,
  * chunk not a multiple of 64), DOS_EALIGN (slot_mem / pinned_stage not 256-byte
  * aligned), DOS_EBUDGET (slot_bytes < n_slots * 12 * slot_params, ring smaller
- * than two chunks), DOS_EHIP. */
+ * than two chunks), DOS_EHIP, DOS_ENOMEM. */
 dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg);
 /* Joins the context's threads and releases the events; NULL is allowed. */
 void dos_ctx_destroy(dos_ctx* ctx);
@@ -313,15 +323,32 @@ void dos_ctx_destroy(dos_ctx* ctx);
  * (plan->n_slots, slot_params and resident are informative: the context's slots
  * and each subgroup's state_loc are what the phase uses).  Errors leave all state
  * untouched when they are detected by validation (DOS_EINVAL, DOS_EALIGN,
- * DOS_ESTATE, DOS_EBUDGET); DOS_EHIP is sticky and state is then undefined. */
+ * DOS_ESTATE, DOS_EBUDGET -- the last also for a phase with more pieces or chunks
+ * than the context was created for); DOS_EHIP is sticky and state is then
+ * undefined.  Allocates nothing, on the device or on the host. */
 dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
                                 const dos_hparams* hp, dos_phase_stats* stats);
 
-/* Measures the rates of dos_cost_model on this machine with the context's own
- * slots, streams and worker threads: pinned copies each way under duplex load,
- * the device kernel over one slot, the host update over a temporary 1.9 GB host
- * buffer (larger than the caches; allocated and freed inside the call, which is
- * not part of the update phase). */
+/* Measures the inputs of the performance model (Section 4.2: the link rate B,
+ * the GPU and CPU update rates U_g and U_c; the downscale rate D_c is reported as
+ * 0 = fused) on this machine, with the context's own slots, streams and worker
+ * threads and through the paths its phases use:
+ *   h2d_Bps, d2h_Bps   pinned copies in both directions at once (the paper gives
+ *                      one B; the directions differ under duplex load), between
+ *                      slot 0 and the upload ring -- or, for a context without a
+ *                      ring, pinned memory obtained for the duration of the call;
+ *   gpu_params_per_s, launch_overhead_s   the fused kernel over one slot;
+ *   cpu_params_per_s   the host update with all worker threads over a temporary
+ *                      1.9 GB host buffer (larger than the caches), its 16-bit
+ *                      output going where the phases send it: with
+ *                      DOS_CTX_UPLOAD_DIRECT into device memory through the PCIe
+ *                      BAR (the staging slots serve as the target), otherwise
+ *                      into host memory as into the upload ring.
+ * The rates are stand-alone peaks: what staged traffic takes away from the host
+ * cores when both lanes run (Section 5.4, CPU cores per GPU) is left to
+ * dos_cost_model_observe.  Not part of the update phase: the call allocates and
+ * frees its temporary buffers and overwrites the staging slots and the ring.
+ * Errors: DOS_EBUDGET (no slot, or slot / ring below 1 MiB), DOS_ENOMEM, DOS_EHIP. */
 dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
 
 /* Timeline of the GPU lane of the context's last phase (contexts created with
@@ -333,7 +360,10 @@ dos_status dos_calibrate(dos_ctx* ctx, dos_cost_model* out);
  * had into *n_pieces (0 when nothing was timed). */
 dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pieces, int32_t* n_pieces);
 
-/* Feeds what the phase that produced `st` actually reached back into `cm`.
+/* Feeds what the phase that produced `st` actually reached back into `cm`
+ * (Section 4.2 takes B, U_g, U_c as constants measured once; Section 5.4, "CPU
+ * cores per GPU", shows that host update and transfers slow each other down
+ * when they share the host's memory system -- this call measures by how much).
  * Host lane: its time is fitted as (N_C + cost * staged bytes) / cpu_params_per_s
  * over the phases seen so far (older ones fade), which separates the host cores'
  * own rate from what the GPU lane's traffic takes away from them as soon as two
@@ -358,23 +388,6 @@ dos_status dos_device_large_bar(int32_t device, int32_t* yes);
 /* Pinned (page-locked) host memory of exactly `bytes` bytes, 4 KiB aligned. */
 dos_status dos_pinned_alloc(void** out, uint64_t bytes);
 dos_status dos_pinned_free(void* ptr);
-
-/* Measurement aid: a plain device-to-device copy kernel (reads `bytes`, writes
- * `bytes`; multiple of 16; both pointers device memory, 16-byte aligned),
- * asynchronous on hip_stream.  Hardware traffic counters read for this kernel
- * give the scale of the same counters read for the AdamW kernel. */
-dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
-
-/* Measurement aid: the default launch of dos_adam_step over a device-resident
- * subgroup with parts taken out -- mode 0 performs only its loads (14 B/param),
- * mode 1 only its stores (14 B/param; p, m, v and p_lp become 0), mode 2 loads
- * and stores without the arithmetic (it flips the sign of p, m, v: modes 1 and 2
- * destroy the optimizer state they run on).  The rates of
- * modes 0 and 1 are what the memory system reaches in each direction alone; the
- * AdamW kernel's mixed rate is judged against them.  lds_bytes as in
- * dos_launch_cfg (0 = the default cap on waves per CU, negative = no cap).
- * Elements past the last multiple of four are not touched. */
-dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream);
 
 /* Asks the kernel to back a range of ordinary (pageable) host memory with huge
  * pages where it can (Linux madvise MADV_HUGEPAGE on the whole pages inside the

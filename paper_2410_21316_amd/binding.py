@@ -10,7 +10,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdos.so")
 
-DOS_OK, DOS_EINVAL, DOS_EALIGN, DOS_EBUDGET, DOS_EHIP, DOS_ESTATE = 0, -1, -2, -3, -4, -5
+DOS_OK, DOS_EINVAL, DOS_EALIGN, DOS_EBUDGET, DOS_EHIP, DOS_ESTATE, DOS_ENOMEM = 0, -1, -2, -3, -4, -5, -6
 DOS_HOST_PINNED, DOS_DEVICE, DOS_HOST_PAGEABLE = 0, 1, 2
 DOS_ON_CPU, DOS_ON_GPU = 0, 1
 DOS_OPT_ADAMW, DOS_OPT_ADAGRAD, DOS_OPT_RMSPROP = 0, 1, 2
@@ -98,8 +98,6 @@ SIGNATURES = {
     "dos_device_large_bar": (C.c_int, [C.c_int32, C.POINTER(C.c_int32)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
-    "dos_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
-    "dos_probe_adam_traffic": (C.c_int, [C.POINTER(dos_subgroup), C.c_int32, C.c_int32, C.c_void_p]),
     "dos_host_advise_hugepages": (C.c_int, [C.c_void_p, C.c_uint64]),
     "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
@@ -276,15 +274,6 @@ def dos_pinned_alloc(nbytes: int) -> int:
 
 def dos_pinned_free(ptr: int) -> None:
     check(load().dos_pinned_free(C.c_void_p(ptr)), "dos_pinned_free")
-
-
-def dos_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
-    check(load().dos_probe_copy(C.c_void_p(dst), C.c_void_p(src), int(nbytes), C.c_void_p(stream)), "dos_probe_copy")
-
-
-def dos_probe_adam_traffic(sg: dos_subgroup, mode: int, stream: int = 0, lds_bytes: int = 0) -> None:
-    check(load().dos_probe_adam_traffic(C.byref(sg), int(mode), int(lds_bytes), C.c_void_p(stream)),
-          "dos_probe_adam_traffic")
 
 
 def dos_host_advise_hugepages(ptr: int, nbytes: int) -> bool:

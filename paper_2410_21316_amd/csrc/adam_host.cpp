@@ -213,15 +213,27 @@ extern "C" dos_status dos_adam_step_host(const dos_subgroup* sg, const dos_hpara
   float* const m = sg->m;  // NULL for the rules without a first moment: never offset
   // static split on 64-element boundaries
   const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
+  // Slices that found no thread (the system refused one) are updated by the calling thread, so
+  // the call always completes the whole subgroup and nothing leaves it as an exception.
   std::vector<std::thread> pool;
-  pool.reserve(T);
-  for (int t = 0; t < T; ++t) {
+  int started = 0;
+  try {
+    pool.reserve(T);
+    for (; started < T; ++started) {
+      const uint64_t lo = (uint64_t)started * per;
+      if (lo >= n) break;
+      const uint64_t cnt = (lo + per <= n) ? per : n - lo;
+      pool.emplace_back([=]() {
+        dos::host_adam_range(sg->p + lo, m ? m + lo : nullptr, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
+      });
+    }
+  } catch (...) {
+  }
+  for (int t = started; t < T; ++t) {
     const uint64_t lo = (uint64_t)t * per;
     if (lo >= n) break;
     const uint64_t cnt = (lo + per <= n) ? per : n - lo;
-    pool.emplace_back([=]() {
-      dos::host_adam_range(sg->p + lo, m ? m + lo : nullptr, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
-    });
+    dos::host_adam_range(sg->p + lo, m ? m + lo : nullptr, sg->v + lo, sg->g + lo, sg->p_lp + lo, cnt, s);
   }
   for (auto& th : pool) th.join();
   return DOS_OK;

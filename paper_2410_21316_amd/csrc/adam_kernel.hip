@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include "dos_internal.h"
+#include "tile_access.h"
 
 namespace dos {
 namespace {
@@ -35,10 +36,6 @@ constexpr int64_t kDefaultLdsThrottle = 14848;
 // 11 or 17 waves).
 constexpr int64_t kDefaultLdsThrottleTwoArrays = 10923;
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T* ptr) {
   if constexpr (NT) return __builtin_nontemporal_load(ptr);
@@ -51,43 +48,6 @@ __device__ __forceinline__ void st(T* ptr, T val) {
   static_assert(SP == 0 || SP == 1, "system-scope store policies exist in the untiled layout only");
   if constexpr (SP == 1) __builtin_nontemporal_store(val, ptr);
   else *ptr = val;
-}
-
-// The untiled layout addresses its tile through buffer descriptors: the cache
-// policy of every access is an operand of the compiler's buffer builtins (bit 0
-// sc0, bit 1 nt, bit 4 sc1 on gfx950), so the compiler, not hand-written
-// instructions, keeps the wait states and counters right; and the descriptor's
-// size makes the hardware drop accesses past the last whole quad, so the ragged
-// last tile needs no branch (loads return 0, stores are discarded).
-template <bool NTL>
-constexpr int load_aux() { return NTL ? 2 : 0; }
-// Store policies: 0 plain, 1 non-temporal, 2 non-temporal at system scope without
-// the wave-level bit (sc1 nt), 3 non-temporal at system scope (sc0 sc1 nt).
-template <int SP>
-constexpr int store_aux() { return SP == 0 ? 0 : SP == 1 ? 2 : SP == 2 ? 18 : 19; }
-
-// Descriptor over `bytes` bytes starting at `base` (wave-uniform): raw buffer, no
-// stride, 32-bit data format.  A tile is a few KiB, so clamping the size of what
-// is left of an array to 32 bits never cuts into the tile.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, uint64_t bytes) {
-  const uint32_t rec = bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes;
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)rec, 0x00020000);
-}
-template <bool NTL>
-__device__ __forceinline__ f32x4 buf_ld4(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, load_aux<NTL>()));
-}
-template <bool NTL>
-__device__ __forceinline__ u32x2 buf_ld2(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, load_aux<NTL>());
-}
-template <int SP>
-__device__ __forceinline__ void buf_st4(__amdgpu_buffer_rsrc_t r, uint32_t off, f32x4 val) {
-  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), r, (int)off, 0, store_aux<SP>());
-}
-template <int SP>
-__device__ __forceinline__ void buf_st2(__amdgpu_buffer_rsrc_t r, uint32_t off, u32x2 val) {
-  __builtin_amdgcn_raw_buffer_store_b64(val, r, (int)off, 0, store_aux<SP>());
 }
 
 // binary32 -> bf16 bit pattern, round to nearest even; NaN kept as quiet NaN.
@@ -343,56 +303,6 @@ __global__ __launch_bounds__(256) void pull_copy_kernel(u32x4* __restrict__ dst,
   if (blockIdx.x == 0 && t < n16) dst16[t] = src16[t];
 }
 
-// Plain device-to-device copy, 16 bytes per lane, one tile per block: the
-// known-size reference against which hardware traffic counters are scaled.
-__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
-                                                         uint64_t n_vec) {
-  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_vec) dst[i] = src[i];
-}
-
-// The default AdamW launch with parts taken out, for measuring what bounds it:
-// MODE 0 only performs the loads (14 B/param), MODE 1 only the stores (14 B/param,
-// constants), MODE 2 loads and stores without the arithmetic.
-template <int MODE>
-__global__ __launch_bounds__(64) void probe_traffic_kernel(float* __restrict__ p, float* __restrict__ m,
-                                                           float* __restrict__ v, const uint16_t* __restrict__ g,
-                                                           uint16_t* __restrict__ p_lp, uint64_t n) {
-  const uint64_t whole = (n >> 2) << 2;
-  const uint64_t e0 = (uint64_t)blockIdx.x * blockDim.x * 4;
-  const uint64_t left = whole > e0 ? whole - e0 : 0;
-  const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rm = tile_rsrc(m + e0, left * 4),
-                               rv = tile_rsrc(v + e0, left * 4), rg = tile_rsrc(g + e0, left * 2),
-                               ro = tile_rsrc(p_lp + e0, left * 2);
-  const uint32_t off4 = threadIdx.x * 16, off2 = threadIdx.x * 8;
-  f32x4 P = {0.f, 0.f, 0.f, 0.f}, M = P, V = P;
-  u32x2 G = {0u, 0u};
-  if (MODE != 1) {
-    G = buf_ld2<true>(rg, off2);
-    P = buf_ld4<true>(rp, off4);
-    M = buf_ld4<true>(rm, off4);
-    V = buf_ld4<true>(rv, off4);
-  }
-  if (MODE == 0) {
-    // never true for the finite data the probe runs on; keeps the loads alive
-    if (P.x != P.x && M.y != M.y && V.z != V.z && G.x == 0x7FC17FC1u) buf_st2<3>(ro, off2, G);
-    return;
-  }
-  if (MODE == 2) {
-    // one cheap operation per element, so that no part of the store-back is a no-op the
-    // compiler may drop
-    P = -P;
-    M = -M;
-    V = -V;
-    G.x ^= 0x00010001u;
-    G.y ^= 0x00010001u;
-  }
-  buf_st4<3>(rm, off4, M);
-  buf_st4<3>(rv, off4, V);
-  buf_st4<3>(rp, off4, P);
-  buf_st2<3>(ro, off2, G);
-}
-
 template <bool NTL, int NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStream_t st_, float* p, float* m, float* v,
                          const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s, uint32_t xcd_shift) {
@@ -486,44 +396,6 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     note_hip_error((int)e, "launch of the fused AdamW kernel");
-    return DOS_EHIP;
-  }
-  return DOS_OK;
-}
-
-dos_status launch_probe_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
-  const uint64_t n_vec = bytes >> 4;
-  if (n_vec == 0) return DOS_OK;
-  const uint64_t blocks = (n_vec + 255) / 256;
-  if (blocks > 0x7FFFFFFFull) return DOS_EINVAL;
-  hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
-                     reinterpret_cast<u32x4*>(dst), reinterpret_cast<const u32x4*>(src), n_vec);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    note_hip_error((int)e, "launch of the probe copy kernel");
-    return DOS_EHIP;
-  }
-  return DOS_OK;
-}
-
-dos_status launch_probe_traffic(const dos_subgroup* sg, int mode, int lds_bytes, void* stream) {
-  const uint64_t n_quads = sg->n >> 2;
-  if (lds_bytes > 65536) return DOS_EINVAL;
-  const size_t lds = lds_bytes == 0 ? (size_t)kDefaultLdsThrottle : lds_bytes < 0 ? 0 : (size_t)lds_bytes;
-  if (n_quads == 0) return DOS_OK;
-  const uint64_t blocks = (n_quads + 63) / 64;
-  if (blocks > 0x7FFFFFFFull || mode < 0 || mode > 2) return DOS_EINVAL;
-  hipStream_t st_ = reinterpret_cast<hipStream_t>(stream);
-  const dim3 grid((unsigned)blocks), block(64);
-  if (mode == 0)
-    hipLaunchKernelGGL(probe_traffic_kernel<0>, grid, block, lds, st_, sg->p, sg->m, sg->v, sg->g, sg->p_lp, sg->n);
-  else if (mode == 1)
-    hipLaunchKernelGGL(probe_traffic_kernel<1>, grid, block, lds, st_, sg->p, sg->m, sg->v, sg->g, sg->p_lp, sg->n);
-  else
-    hipLaunchKernelGGL(probe_traffic_kernel<2>, grid, block, lds, st_, sg->p, sg->m, sg->v, sg->g, sg->p_lp, sg->n);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    note_hip_error((int)e, "launch of a probe traffic kernel");
     return DOS_EHIP;
   }
   return DOS_OK;

@@ -79,22 +79,6 @@ dos_status dos_pinned_free(void* ptr) {
   return DOS_OK;
 }
 
-dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream) {
-  if (bytes == 0) return DOS_OK;
-  if (!dst_dev || !src_dev || (bytes & 15)) return DOS_EINVAL;
-  if (((uintptr_t)dst_dev | (uintptr_t)src_dev) & 15) return DOS_EALIGN;
-  return dos::launch_probe_copy(dst_dev, src_dev, bytes, hip_stream);
-}
-
-dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream) {
-  dos_status rc = dos::check_subgroup_pointers(sg);
-  if (rc != DOS_OK) return rc;
-  if (mode < 0 || mode > 2) return DOS_EINVAL;
-  if (sg->n == 0) return DOS_OK;
-  if (sg->state_loc != DOS_DEVICE || sg->grad_loc != DOS_DEVICE) return DOS_ESTATE;
-  return dos::launch_probe_traffic(sg, mode, lds_bytes, hip_stream);
-}
-
 dos_status dos_host_advise_hugepages(void* ptr, uint64_t bytes) {
   if (!ptr && bytes) return DOS_EINVAL;
 #if defined(__linux__) && defined(MADV_HUGEPAGE)
@@ -113,21 +97,27 @@ dos_status dos_host_prefault(void* ptr, uint64_t bytes, int32_t threads) {
   const uint64_t page = 4096;
   const uint64_t pages = (bytes + page - 1) / page;
   if ((uint64_t)T > pages) T = (int)pages;
-  std::vector<std::thread> pool;
   std::atomic<uint64_t> sink{0};
   volatile unsigned char* base = static_cast<volatile unsigned char*>(ptr);
-  for (int t = 0; t < T; ++t) {
+  auto touch = [=, &sink](int t) {
     const uint64_t lo = pages * t / T, hi = pages * (t + 1) / T;
-    pool.emplace_back([=, &sink] {
-      uint64_t acc = 0;
-      for (uint64_t pg = lo; pg < hi; ++pg) {
-        const unsigned char b = base[pg * page];
-        base[pg * page] = b;  // a write fault gives the page real memory, not the shared zero page
-        acc += b;
-      }
-      sink.fetch_add(acc, std::memory_order_relaxed);
-    });
+    uint64_t acc = 0;
+    for (uint64_t pg = lo; pg < hi; ++pg) {
+      const unsigned char b = base[pg * page];
+      base[pg * page] = b;  // a write fault gives the page real memory, not the shared zero page
+      acc += b;
+    }
+    sink.fetch_add(acc, std::memory_order_relaxed);
+  };
+  // shares that found no thread are touched by the calling thread: nothing leaves as an exception
+  std::vector<std::thread> pool;
+  int started = 0;
+  try {
+    pool.reserve(T);
+    for (; started < T; ++started) pool.emplace_back(touch, started);
+  } catch (...) {
   }
+  for (int t = started; t < T; ++t) touch(t);
   for (auto& th : pool) th.join();
   return DOS_OK;
 }
@@ -140,12 +130,13 @@ const char* dos_strerror(dos_status s) {
     case DOS_EBUDGET: return "GPU budget or staging memory too small";
     case DOS_EHIP: return "HIP call failed";
     case DOS_ESTATE: return "memory location does not fit the requested target";
+    case DOS_ENOMEM: return "host memory or a thread could not be obtained";
   }
   return "unknown status";
 }
 
 const char* dos_last_hip_error(void) { return dos::g_hip_error; }
 
-int32_t dos_version(void) { return 110; }
+int32_t dos_version(void) { return 120; }
 
 }  // extern "C"

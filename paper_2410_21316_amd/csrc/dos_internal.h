@@ -36,14 +36,6 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
 // host memory and writes them to device memory; both pointers 16-byte aligned.
 dos_status launch_pull_copy_u16(uint16_t* dst_dev, const uint16_t* src_host, uint64_t n, void* stream);
 
-// Plain device-to-device copy kernel over `bytes` (multiple of 16) bytes.
-dos_status launch_probe_copy(void* dst, const void* src, uint64_t bytes, void* stream);
-
-// The default AdamW launch over a device-resident subgroup with only its loads
-// (mode 0), only its stores (mode 1) or both but no arithmetic (mode 2); lds_bytes
-// as in dos_launch_cfg.
-dos_status launch_probe_traffic(const dos_subgroup* sg, int mode, int lds_bytes, void* stream);
-
 // Host update of elements [0, n) on the calling thread (vectorised, bit-identical
 // to the device kernel).
 void host_adam_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, uint64_t n,

@@ -34,6 +34,7 @@
 #include <chrono>
 #include <condition_variable>
 #include <mutex>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -48,6 +49,10 @@ inline double secs(clk::time_point a, clk::time_point b) {
 
 constexpr int kMaxSlots = 16;
 constexpr int kProfPieces = 4096;  // pieces per phase that can be timed individually
+// Capacity of the per-phase work lists, reserved when the context is created so that a
+// phase never grows them: a phase that would need more is refused (DOS_EBUDGET).
+constexpr size_t kMaxChunks = (size_t)1 << 16;
+constexpr size_t kMaxPieces = (size_t)1 << 14;
 
 struct Chunk {  // a piece of a CPU-planned subgroup
   int sg;
@@ -80,6 +85,8 @@ struct dos_ctx {
   // profiling events
   std::vector<hipEvent_t> prof;  // 6 per piece
   std::vector<float> timeline;   // the last phase's event times, 6 per piece (ms since t0)
+  std::vector<std::pair<double, double>> iv_up, iv_down;  // copy intervals of the last phase (statistics)
+  hipEvent_t cal_ev[4] = {nullptr, nullptr, nullptr, nullptr};  // timing events of dos_calibrate
   hipEvent_t t0 = nullptr;  // start of the phase on the H2D stream (origin of the profile timeline)
   // end of the GPU lane: tail[0], tail[1] close the H2D and compute streams, lane_end follows both
   // and the last flush on the D2H stream; the driver thread sleeps on it
@@ -360,21 +367,25 @@ void destroy(dos_ctx* c) {
   for (auto e : c->prof)
     if (e) (void)hipEventDestroy(e);
   if (c->t0) (void)hipEventDestroy(c->t0);
+  for (hipEvent_t e : c->cal_ev)
+    if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : {c->tail[0], c->tail[1], c->lane_end})
     if (e) (void)hipEventDestroy(e);
   delete c;
 }
 
 // Length of the union of [a,b) intervals intersected with the union of another set.
-double overlap_of_unions(std::vector<std::pair<double, double>> a, std::vector<std::pair<double, double>> b) {
+// Works in place on the two lists (sorted and merged where they stand): no allocation.
+double overlap_of_unions(std::vector<std::pair<double, double>>& a, std::vector<std::pair<double, double>>& b) {
   auto merge = [](std::vector<std::pair<double, double>>& v) {
+    if (v.empty()) return;
     std::sort(v.begin(), v.end());
-    std::vector<std::pair<double, double>> out;
-    for (auto& iv : v) {
-      if (!out.empty() && iv.first <= out.back().second) out.back().second = std::max(out.back().second, iv.second);
-      else out.push_back(iv);
+    size_t w = 0;
+    for (size_t r = 1; r < v.size(); ++r) {
+      if (v[r].first <= v[w].second) v[w].second = std::max(v[w].second, v[r].second);
+      else v[++w] = v[r];
     }
-    v.swap(out);
+    v.resize(w + 1);
   };
   merge(a);
   merge(b);
@@ -390,9 +401,9 @@ double overlap_of_unions(std::vector<std::pair<double, double>> a, std::vector<s
 
 }  // namespace
 
-extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
-  if (!out) return DOS_EINVAL;
-  *out = nullptr;
+namespace {
+
+dos_status ctx_create(dos_ctx** out, const dos_ctx_config* cfg, dos_ctx*& c) {
   if (!cfg || cfg->host_threads < 1 || cfg->host_threads > 1024 || cfg->n_slots < 0 || cfg->n_slots > kMaxSlots)
     return DOS_EINVAL;
   if (cfg->n_slots > 0) {
@@ -421,7 +432,7 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     }
     if (!large_bar) return DOS_ESTATE;
   }
-  dos_ctx* c = new dos_ctx();
+  c = new dos_ctx();
   c->device = cfg->device;
   c->flags = cfg->flags;
   c->T = cfg->host_threads;
@@ -441,6 +452,7 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     dos::note_hip_error((int)e, what);
     (void)hipGetLastError();
     destroy(c);
+    c = nullptr;
     return DOS_EHIP;
   };
   hipError_t e;
@@ -467,14 +479,18 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
     if ((e = hipEventCreateWithFlags(ev, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
   if ((e = hipEventCreateWithFlags(&c->lane_end, hipEventDisableTiming | ((c->flags & DOS_CTX_SPIN_WAIT) ? 0u : (unsigned)hipEventBlockingSync))) != hipSuccess)
     return fail(e, "hipEventCreate");
+  for (hipEvent_t& ev : c->cal_ev)
+    if ((e = hipEventCreate(&ev)) != hipSuccess) return fail(e, "hipEventCreate");
   if (c->flags & DOS_CTX_PROFILE) {
     c->prof.assign((size_t)kProfPieces * 6, nullptr);
     c->timeline.reserve((size_t)kProfPieces * 6);
+    c->iv_up.reserve(kProfPieces);
+    c->iv_down.reserve(kProfPieces);
     for (auto& ev : c->prof)
       if ((e = hipEventCreate(&ev)) != hipSuccess) return fail(e, "hipEventCreate");
   }
-  c->chunks.reserve(1 << 16);
-  c->pieces.reserve(1 << 14);
+  c->chunks.reserve(kMaxChunks);
+  c->pieces.reserve(kMaxPieces);
   c->lane_times.resize(c->T);
   c->workers.reserve(c->T);
   for (int t = 0; t < c->T; ++t) c->workers.emplace_back(worker_main, c, t);
@@ -483,12 +499,36 @@ extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
   return DOS_OK;
 }
 
+}  // namespace
+
+extern "C" dos_status dos_ctx_create(dos_ctx** out, const dos_ctx_config* cfg) {
+  if (!out) return DOS_EINVAL;
+  *out = nullptr;
+  dos_ctx* c = nullptr;
+  // Containers and threads are created here; a failure of either must not leave the C boundary as
+  // an exception.  destroy() joins whatever threads were started.
+  try {
+    return ctx_create(out, cfg, c);
+  } catch (...) {
+    if (c) {
+      try {
+        destroy(c);
+      } catch (...) {
+      }
+    }
+    *out = nullptr;
+    return DOS_ENOMEM;
+  }
+}
+
 extern "C" void dos_ctx_destroy(dos_ctx* ctx) {
   if (ctx) destroy(ctx);
 }
 
-extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
-                                           const dos_hparams* hp, dos_phase_stats* stats) {
+namespace {
+
+dos_status run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan, const dos_hparams* hp,
+                            dos_phase_stats* stats) {
   const auto t_entry = clk::now();
   if (!c || !plan || n_sg < 0 || (n_sg > 0 && (!sgs || !plan->target || !plan->order))) return DOS_EINVAL;
   if (c->sticky != DOS_OK) return c->sticky;
@@ -527,6 +567,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       // the host cores read and write it in place: pinned or pageable, but not device memory
       if (sg.state_loc == DOS_DEVICE || sg.grad_loc == DOS_DEVICE) return DOS_ESTATE;
       if (c->ring_n < 2 && !(c->flags & DOS_CTX_UPLOAD_DIRECT)) return DOS_EBUDGET;
+      if ((sg.n + c->chunk_params - 1) / c->chunk_params > kMaxChunks - chunks.size()) return DOS_EBUDGET;
       for (uint64_t off = 0; off < sg.n; off += c->chunk_params)
         chunks.push_back({i, off, std::min(c->chunk_params, sg.n - off)});
       params_cpu += sg.n;
@@ -540,6 +581,7 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       if (sg.state_loc == DOS_HOST_PAGEABLE || sg.grad_loc == DOS_HOST_PAGEABLE) return DOS_ESTATE;
       if (c->n_slots < 1) return DOS_EBUDGET;
       if (sg.grad_loc == DOS_HOST_PINNED && !c->slots_hold_grads) return DOS_EBUDGET;
+      if ((sg.n + c->slot_params - 1) / c->slot_params > kMaxPieces - pieces.size()) return DOS_EBUDGET;
       for (uint64_t off = 0; off < sg.n; off += c->slot_params)
         pieces.push_back({i, off, std::min(c->slot_params, sg.n - off)});
       params_gpu += sg.n;
@@ -724,7 +766,10 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
       }
     c->timeline.clear();
     if (prof && !pieces.empty()) {
-      std::vector<std::pair<double, double>> up, down;
+      // (pieces.size() <= kProfPieces here, which is what the two lists were reserved for)
+      std::vector<std::pair<double, double>>&up = c->iv_up, &down = c->iv_down;
+      up.clear();
+      down.clear();
       double hb = 0, db = 0, gb = 0;
       bool ok = true;
       for (size_t j = 0; j < pieces.size() && ok; ++j) {
@@ -748,13 +793,28 @@ extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_
         stats->h2d_busy_s = hb;
         stats->d2h_busy_s = db;
         stats->gpu_busy_s = gb;
-        stats->duplex_overlap_s = overlap_of_unions(up, down);
+        // (pieces are processed in order on each stream: first and last copy bound the span)
         stats->h2d_span_s = up.back().second - up.front().first;
         stats->d2h_span_s = down.back().second - down.front().first;
+        stats->duplex_overlap_s = overlap_of_unions(up, down);
       }
     }
   }
   return DOS_OK;
+}
+
+}  // namespace
+
+extern "C" dos_status dos_run_update_phase(dos_ctx* c, dos_subgroup* sgs, int32_t n_sg, const dos_plan* plan,
+                                           const dos_hparams* hp, dos_phase_stats* stats) {
+  try {
+    return run_update_phase(c, sgs, n_sg, plan, hp, stats);
+  } catch (...) {
+    // nothing in the phase allocates, so nothing is expected here; should a lock or a wait fail all
+    // the same, the state of the subgroups is unknown
+    if (c) c->sticky = DOS_EHIP;
+    return DOS_ENOMEM;
+  }
 }
 
 extern "C" dos_status dos_ctx_last_timeline(const dos_ctx* c, float* ms6, int32_t max_pieces, int32_t* n_pieces) {
@@ -766,34 +826,56 @@ extern "C" dos_status dos_ctx_last_timeline(const dos_ctx* c, float* ms6, int32_
   return DOS_OK;
 }
 
-// Rates of the cost model measured with the context's own resources.
-extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
-  if (!c || !out) return DOS_EINVAL;
+// Rates of the cost model measured with the context's own resources (the inputs of the
+// performance model, Section 4.2: B per direction, U_g, U_c; D_c is zero because the
+// downscale is fused into the host update).
+namespace {
+
+dos_status calibrate(dos_ctx* c, dos_cost_model* out) {
   if (c->sticky != DOS_OK) return c->sticky;
-  if (c->n_slots < 1 || c->ring_n < 2) return DOS_EBUDGET;
+  if (c->n_slots < 1) return DOS_EBUDGET;
   HIP_TRY(c, hipSetDevice(c->device), "hipSetDevice");
   memset(out, 0, sizeof *out);
-  const uint64_t stage_bytes = (uint64_t)c->ring_n * c->chunk_params * 2;
-  const uint64_t half = (stage_bytes / 2) & ~(uint64_t)255;
   const uint64_t slot_bytes = c->slot_stride;
-  // the device side of both copies sits in slot 0 (first and second half)
-  const uint64_t nbytes = std::min<uint64_t>(half, (slot_bytes / 2) & ~(uint64_t)255);
+  const uint64_t stage_bytes = (uint64_t)c->ring_n * c->chunk_params * 2;
+
+  // ---- host link, both directions at once.  Host side: the upload ring, or (contexts without
+  // one) pinned memory obtained for the duration of the measurement.  Device side: the two halves
+  // of slot 0.
+  uint64_t nbytes = (slot_bytes / 2) & ~(uint64_t)255;
+  char* pinned_tmp = nullptr;
+  char *host_a, *host_b;
+  if (c->ring_n >= 2) {
+    const uint64_t half = (stage_bytes / 2) & ~(uint64_t)255;
+    nbytes = std::min(nbytes, half);
+    host_a = c->stage;
+    host_b = c->stage + half;
+  } else {
+    nbytes = std::min<uint64_t>(nbytes, (uint64_t)256 << 20);
+    if (nbytes >= (1u << 20)) {
+      void* q = nullptr;
+      HIP_TRY(c, hipHostMalloc(&q, 2 * nbytes, hipHostMallocDefault), "hipHostMalloc for the link calibration");
+      pinned_tmp = (char*)q;
+    }
+    host_a = pinned_tmp;
+    host_b = pinned_tmp + nbytes;
+  }
   if (nbytes < (1u << 20)) return DOS_EBUDGET;
+  auto release = [&] {
+    if (pinned_tmp) (void)hipHostFree(pinned_tmp);
+    pinned_tmp = nullptr;
+  };
   char* dev_a = c->slot_mem;
   char* dev_b = c->slot_mem + nbytes;
-  char* host_a = c->stage;
-  char* host_b = c->stage + half;
-  memset(c->stage, 0, stage_bytes);
-  HIP_TRY(c, hipMemsetAsync(c->slot_mem, 0, slot_bytes, c->comp), "hipMemsetAsync");
-  HIP_TRY(c, hipStreamSynchronize(c->comp), "hipStreamSynchronize");
-
-  hipEvent_t ev[4];
-  for (auto& e : ev) HIP_TRY(c, hipEventCreate(&e), "hipEventCreate");
-  auto cleanup = [&] { for (auto& e : ev) (void)hipEventDestroy(e); };
+  memset(host_a, 0, nbytes);
+  memset(host_b, 0, nbytes);
+  hipEvent_t* ev = c->cal_ev;
+  hipError_t e = hipMemsetAsync(c->slot_mem, 0, slot_bytes, c->comp);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->comp);
   const int reps = (int)std::max<uint64_t>(2, std::min<uint64_t>(64, ((uint64_t)2 << 30) / nbytes));
   // warm-up, then both directions at once
-  for (int pass = 0; pass < 2; ++pass) {
-    hipError_t e = hipEventRecord(ev[0], c->h2d);
+  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {
+    e = hipEventRecord(ev[0], c->h2d);
     if (e == hipSuccess) e = hipEventRecord(ev[2], c->d2h);
     for (int r = 0; r < (pass ? reps : 1) && e == hipSuccess; ++r) {
       e = hipMemcpyAsync(dev_a, host_a, nbytes, hipMemcpyHostToDevice, c->h2d);
@@ -803,22 +885,16 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     if (e == hipSuccess) e = hipEventRecord(ev[3], c->d2h);
     if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);
     if (e == hipSuccess) e = hipStreamSynchronize(c->d2h);
-    if (e != hipSuccess) {
-      cleanup();
-      HIP_TRY(c, e, "calibration copies");
-    }
   }
   float ms_up = 0, ms_down = 0;
-  hipError_t e = hipEventElapsedTime(&ms_up, ev[0], ev[1]);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms_up, ev[0], ev[1]);
   if (e == hipSuccess) e = hipEventElapsedTime(&ms_down, ev[2], ev[3]);
-  if (e != hipSuccess) {
-    cleanup();
-    HIP_TRY(c, e, "hipEventElapsedTime");
-  }
+  release();
+  HIP_TRY(c, e, "calibration copies");
   out->h2d_Bps = (double)nbytes * reps / (ms_up * 1e-3);
   out->d2h_Bps = (double)nbytes * reps / (ms_down * 1e-3);
 
-  // device kernel over slot 0: five arrays carved out of the slot
+  // ---- device kernel over slot 0: five arrays carved out of the slot
   {
     const uint64_t n = (slot_bytes / 28) & ~(uint64_t)63;
     float* p = (float*)c->slot_mem;
@@ -835,11 +911,8 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     if (he == hipSuccess) he = hipStreamSynchronize(c->comp);
     float ms = 0;
     if (he == hipSuccess) he = hipEventElapsedTime(&ms, ev[0], ev[1]);
-    if (k != DOS_OK || he != hipSuccess) {
-      cleanup();
-      if (k != DOS_OK) return k;
-      HIP_TRY(c, he, "calibration kernel");
-    }
+    if (k != DOS_OK) return k;
+    HIP_TRY(c, he, "calibration kernel");
     out->gpu_params_per_s = (double)n * kreps / (ms * 1e-3);
     // launch overhead: the same kernel over 64 elements
     he = hipEventRecord(ev[0], c->comp);
@@ -847,27 +920,35 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     if (he == hipSuccess) he = hipEventRecord(ev[1], c->comp);
     if (he == hipSuccess) he = hipStreamSynchronize(c->comp);
     if (he == hipSuccess) he = hipEventElapsedTime(&ms, ev[0], ev[1]);
-    if (k != DOS_OK || he != hipSuccess) {
-      cleanup();
-      if (k != DOS_OK) return k;
-      HIP_TRY(c, he, "calibration kernel");
-    }
+    if (k != DOS_OK) return k;
+    HIP_TRY(c, he, "calibration kernel");
     out->launch_overhead_s = ms * 1e-3 / 20;
   }
-  cleanup();
 
-  // host update with all worker threads over a temporary buffer far larger than any
-  // last-level cache (64 Mi parameters, 1.9 GB; the upload ring is used instead if
-  // that cannot be had).  A buffer that fits the caches -- on this machine's host the
-  // cores sit on several chiplets with 32 MiB of L3 each, which together hold the
-  // whole ring -- reads three to four times the rate a real subgroup reaches.
+  // ---- host update with all worker threads, through the path the phase will use: with direct
+  // uploads the 16-bit output is stored into device memory through the PCIe BAR (here: into the
+  // staging slots, every thread rewriting its own window of them), otherwise it goes to host memory
+  // as it does into the upload ring.  The state is a temporary buffer far larger than any last-level
+  // cache (64 Mi parameters, 1.9 GB): on this machine's host the cores sit on several chiplets with
+  // 32 MiB of L3 each, and anything ring-sized reads three to four times the rate a real subgroup
+  // reaches.
   {
+    const bool direct = (c->flags & DOS_CTX_UPLOAD_DIRECT) != 0;
+    const int T = c->T;
     uint64_t n = (uint64_t)64 << 20;
     char* big = static_cast<char*>(aligned_alloc(4096, n * 28));
     char* base = big;
     if (!big) {
+      if (c->ring_n < 2) return DOS_ENOMEM;
       n = (stage_bytes / 28) & ~(uint64_t)63;
       base = c->stage;
+    }
+    // device window of each thread for the direct path, in 16-bit words
+    uint16_t* const dev_out = reinterpret_cast<uint16_t*>(c->slot_mem);
+    const uint64_t window = (((uint64_t)c->n_slots * slot_bytes / 2) / (uint64_t)T) & ~(uint64_t)63;
+    if (direct && window < 4096) {
+      if (big) free(big);
+      return DOS_EBUDGET;
     }
     float* p = (float*)base;
     float* m = p + n;
@@ -875,11 +956,18 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
     uint16_t* g = (uint16_t*)(v + n);
     uint16_t* lp = g + n;
     dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f, DOS_OPT_ADAMW};
-    const int T = c->T;
     const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
     // every thread sweeps its own slice `reps` times; reps == 0 fills it (first touch by its owner)
     auto run = [&](int reps) {
       std::vector<std::thread> th;
+      th.reserve(T);
+      struct Joiner {  // threads already started are joined also when starting the next one fails
+        std::vector<std::thread>& v;
+        ~Joiner() {
+          for (auto& t : v)
+            if (t.joinable()) t.join();
+        }
+      } joiner{th};
       for (int t = 0; t < T; ++t) {
         const uint64_t lo = (uint64_t)t * per;
         if (lo >= n) break;
@@ -893,24 +981,54 @@ extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
               lp[i] = 0;
             }
           }
-          for (int r = 0; r < reps; ++r) dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc);
+          for (int r = 0; r < reps; ++r) {
+            if (!direct) {
+              dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc);
+              continue;
+            }
+            uint16_t* const win = dev_out + (uint64_t)t * window;
+            for (uint64_t off = 0; off < cnt; off += window)
+              dos::host_adam_range_streamed(p + lo + off, m + lo + off, v + lo + off, g + lo + off, win,
+                                            std::min(window, cnt - off), sc);
+          }
+          if (direct && reps > 0) {  // drain the posted writes, as the phase's workers do
+            dos::store_fence();
+            (void)*reinterpret_cast<volatile uint16_t*>(dev_out + (uint64_t)t * window);
+          }
         });
       }
-      for (auto& t : th) t.join();
     };
-    run(0);
-    run(1);
-    auto a = clk::now();
-    run(2);
-    const double t2 = secs(a, clk::now());
-    // aim at ~0.2 s of measured work
-    const int hreps = (int)std::max(2.0, std::min(400.0, 0.2 / (t2 / 2.0)));
-    a = clk::now();
-    run(hreps);
-    out->cpu_params_per_s = (double)n * hreps / secs(a, clk::now());
+    double rate = 0;
+    try {
+      run(0);
+      run(1);
+      auto a = clk::now();
+      run(2);
+      const double t2 = secs(a, clk::now());
+      // aim at ~0.2 s of measured work
+      const int hreps = (int)std::max(2.0, std::min(400.0, 0.2 / (t2 / 2.0)));
+      a = clk::now();
+      run(hreps);
+      rate = (double)n * hreps / secs(a, clk::now());
+    } catch (...) {
+      if (big) free(big);
+      return DOS_ENOMEM;
+    }
+    out->cpu_params_per_s = rate;
     if (big) free(big);
     else memset(c->stage, 0, stage_bytes);
   }
   out->downscale_params_per_s = 0.0;
   return DOS_OK;
+}
+
+}  // namespace
+
+extern "C" dos_status dos_calibrate(dos_ctx* c, dos_cost_model* out) {
+  if (!c || !out) return DOS_EINVAL;
+  try {
+    return calibrate(c, out);
+  } catch (...) {
+    return DOS_ENOMEM;
+  }
 }

@@ -92,9 +92,11 @@ extern "C" dos_status dos_plan_cost(const dos_cost_model* cm, const uint64_t* si
   return DOS_OK;
 }
 
-extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only,
-                                         int32_t n_sg, uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
-                                         int32_t mode, int32_t n_resident_max, dos_plan* out) {
+namespace {
+
+dos_status plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only, int32_t n_sg,
+                          uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot, int32_t mode,
+                          int32_t n_resident_max, dos_plan* out) {
   if (!valid_cost_model(cm) || !out || n_sg < 0 || n_resident_max < 0) return DOS_EINVAL;
   if (mode != DOS_PLAN_STRIDE && mode != DOS_PLAN_BALANCED) return DOS_EINVAL;
   if (bytes_per_param_slot != 12 && bytes_per_param_slot != 14) return DOS_EINVAL;
@@ -233,6 +235,19 @@ extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_
     if (out->resident) out->resident[i] = resident[i];
   }
   return DOS_OK;
+}
+
+}  // namespace
+
+extern "C" dos_status dos_plan_subgroups(const dos_cost_model* cm, const uint64_t* sizes, const uint8_t* cpu_only,
+                                         int32_t n_sg, uint64_t gpu_budget_bytes, int32_t bytes_per_param_slot,
+                                         int32_t mode, int32_t n_resident_max, dos_plan* out) {
+  try {  // the work lists are heap-allocated; the caller's arrays are written last, so an error leaves them as they were
+    return plan_subgroups(cm, sizes, cpu_only, n_sg, gpu_budget_bytes, bytes_per_param_slot, mode, n_resident_max,
+                          out);
+  } catch (...) {
+    return DOS_ENOMEM;
+  }
 }
 
 // Feeds one phase's measured lane rates back into the cost model, so that the

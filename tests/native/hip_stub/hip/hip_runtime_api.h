@@ -6,6 +6,7 @@
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <chrono>
@@ -63,5 +64,14 @@ inline hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpy
 }
 inline hipError_t hipMemsetAsync(void* dst, int v, size_t n, hipStream_t) {
   memset(dst, v, n);
+  return hipSuccess;
+}
+enum { hipHostMallocDefault = 0 };
+inline hipError_t hipHostMalloc(void** p, size_t n, unsigned) {
+  *p = aligned_alloc(4096, (n + 4095) / 4096 * 4096);
+  return *p ? hipSuccess : 2;
+}
+inline hipError_t hipHostFree(void* p) {
+  free(p);
   return hipSuccess;
 }

@@ -2,7 +2,10 @@
 // hip_stub/): the "device" kernels below are the library's own host update, so
 // the result must equal dos_adam_step_host bit for bit.  Built by
 // tests/test_sanitizers.py with phase.cpp, plan.cpp and adam_host.cpp under
-// ASan/UBSan and under TSan (worker pool, upload ring, lane timers).
+// ASan/UBSan and under TSan (worker pool, upload ring, lane timers), and once more
+// with -DDOS_COUNT_ALLOCS, where every heap allocation of the process is counted
+// (operator new replaced here, malloc and friends wrapped by the linker) and the
+// count must not move across dos_run_update_phase: the phase allocates nothing.
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -12,6 +15,49 @@
 #include <vector>
 
 #include "dos_internal.h"
+
+#ifdef DOS_COUNT_ALLOCS
+#include <atomic>
+#include <new>
+static std::atomic<long> g_allocs{0};
+extern "C" {
+void* __real_malloc(size_t);
+void* __real_calloc(size_t, size_t);
+void* __real_realloc(void*, size_t);
+void* __real_aligned_alloc(size_t, size_t);
+int __real_posix_memalign(void**, size_t, size_t);
+void* __wrap_malloc(size_t n) { ++g_allocs; return __real_malloc(n); }
+void* __wrap_calloc(size_t a, size_t b) { ++g_allocs; return __real_calloc(a, b); }
+void* __wrap_realloc(void* q, size_t n) { ++g_allocs; return __real_realloc(q, n); }
+void* __wrap_aligned_alloc(size_t a, size_t n) { ++g_allocs; return __real_aligned_alloc(a, n); }
+int __wrap_posix_memalign(void** q, size_t a, size_t n) { ++g_allocs; return __real_posix_memalign(q, a, n); }
+}
+void* operator new(size_t n) {
+  ++g_allocs;
+  void* q = __real_malloc(n ? n : 1);
+  if (!q) throw std::bad_alloc();
+  return q;
+}
+void* operator new[](size_t n) { return operator new(n); }
+void* operator new(size_t n, std::align_val_t a) {
+  ++g_allocs;
+  void* q = nullptr;
+  if (__real_posix_memalign(&q, (size_t)a < sizeof(void*) ? sizeof(void*) : (size_t)a, n ? n : 1)) throw std::bad_alloc();
+  return q;
+}
+void* operator new[](size_t n, std::align_val_t a) { return operator new(n, a); }
+void operator delete(void* q) noexcept { free(q); }
+void operator delete[](void* q) noexcept { free(q); }
+void operator delete(void* q, size_t) noexcept { free(q); }
+void operator delete[](void* q, size_t) noexcept { free(q); }
+void operator delete(void* q, std::align_val_t) noexcept { free(q); }
+void operator delete[](void* q, std::align_val_t) noexcept { free(q); }
+void operator delete(void* q, size_t, std::align_val_t) noexcept { free(q); }
+void operator delete[](void* q, size_t, std::align_val_t) noexcept { free(q); }
+static long allocs_now() { return g_allocs.load(); }
+#else
+static long allocs_now() { return 0; }
+#endif
 
 namespace dos {
 void note_hip_error(int, const char*) {}
@@ -118,7 +164,12 @@ int main() {
       // the rule rotates with the iteration: AdamW, Adagrad, RMSProp
       dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, step, (int32_t)(it % 3)};
       dos_phase_stats st{};
+      const long allocs_before = allocs_now();
       const dos_status rc = dos_run_update_phase(ctx, sgs.data(), n_sg, &plan, &hp, &st);
+      if (allocs_now() != allocs_before) {
+        fprintf(stderr, "%ld heap allocations inside dos_run_update_phase\n", allocs_now() - allocs_before);
+        return fail("the update phase allocated host memory");
+      }
       if (rc != DOS_OK) {
         fprintf(stderr, "status %d\n", (int)rc);
         return fail("dos_run_update_phase failed");

@@ -54,7 +54,7 @@ def test_struct_layouts_match_the_header(tmp_path):
 
 def test_strerror():
     lib = dos.load()
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         assert lib.dos_strerror(code)
     assert lib.dos_strerror(-2) == b"array not 16-byte aligned"
 

@@ -117,6 +117,82 @@ def test_direct_uploads_are_visible_to_kernels_that_cached_the_old_model(hp):
         st.free()
 
 
+def test_direct_uploads_next_to_gpu_written_ranges_of_a_large_model(hp):
+    """Direct uploads at a size no cache holds: one contiguous 16-bit model of 137M parameters (274 MB, beyond
+    the GPU's L2 and its memory-side cache) cut into four subgroups whose boundaries fall inside cache
+    lines.  Two subgroups are updated by the host cores, which store their part of the model through the
+    PCIe BAR; the two between them are staged and their kernels write the neighbouring ranges of the same
+    model -- partial lines from both sides -- in the same phase.  A reduction kernel on a side stream reads
+    the whole model before every phase (so that the old lines sit wherever the GPU caches them) and right
+    after it; the model must then equal the oracle's, bit for bit."""
+    if not dos.dos_device_large_bar(0):
+        pytest.skip("the device memory is not mapped into the host's address space")
+    from gpu_util import Pinned, assert_parity, oracle_step, round_up
+    sizes = [60_000_008, 4_000_024, 70_000_040, 3_000_008]        # 16-byte aligned slices, not line-aligned
+    targets = [0, 1, 0, 1]
+    total = sum(sizes)
+    assert total * 2 >= 256 * 10**6
+    seed = S.BASE_SEED + 61
+    model = torch.zeros(total, dtype=torch.bfloat16, device="cuda:0")
+    grads = torch.zeros(total, dtype=torch.bfloat16, device="cuda:0")
+    pin = Pinned(sum(3 * round_up(4 * n, 256) + round_up(2 * n, 256) for n in sizes))
+    host, ref, sgs, offs = [], [], [], []
+    off_b, off_e = 0, 0
+    for i, n in enumerate(sizes):
+        h = {}
+        for name in "pmv":
+            h[name] = pin.view(np.float32, off_b, n); off_b += round_up(4 * n, 256)
+        h["g"] = pin.view(np.uint16, off_b, n); off_b += round_up(2 * n, 256)
+        tmp = torch.empty(n, dtype=torch.float32, device="cuda:0")
+        S.fill_chunked(lambda start, count: S.params(seed, i, start, count, "cuda:0"), tmp)
+        h["p"][:] = tmp.cpu().numpy(); h["m"][:] = 0; h["v"][:] = 0
+        del tmp
+        host.append(h)
+        ref.append([h["p"].copy(), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)])
+        lp = model[off_e:off_e + n]
+        gd = grads[off_e:off_e + n]
+        g_ptr = gd.data_ptr() if targets[i] else h["g"].ctypes.data
+        sgs.append(dos.subgroup(h["p"].ctypes.data, h["m"].ctypes.data, h["v"].ctypes.data, g_ptr, lp.data_ptr(), n,
+                                dos.DOS_HOST_PINNED, dos.DOS_DEVICE if targets[i] else dos.DOS_HOST_PINNED))
+        offs.append(off_e)
+        off_e += n
+    ctx = make_context(3, 1 << 20, 8, chunk_params=1 << 20, ring_chunks=0, flags=dos.DOS_CTX_UPLOAD_DIRECT)
+    plan = dos.Plan.manual(targets, None, 3, 1 << 20)
+    side = torch.cuda.Stream()
+    try:
+        for step in (1, 2, 3):
+            gbits = []
+            for i, n in enumerate(sizes):
+                gd = grads[offs[i]:offs[i] + n]
+                S.fill_chunked(lambda start, count: S.grads_bf16(seed, step, i, start, count, "cuda:0", zero_pct=1.0), gd)
+                bits = gd.view(torch.int16).cpu().numpy().view(np.uint16)
+                gbits.append(bits)
+                if not targets[i]:
+                    host[i]["g"][:] = bits
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                before = model.view(torch.int16).to(torch.int64).sum()       # reads (and may cache) the old model
+            side.synchronize()
+            st = ctx.dos_run_update_phase(sgs, plan, dos.hparams(step=step, **hp))
+            with torch.cuda.stream(side):
+                after = model.view(torch.int16).to(torch.int64).sum()        # a kernel, on a stream of its own
+            side.synchronize()
+            want_sum = 0
+            for i, n in enumerate(sizes):
+                oracle_step(ref[i], gbits[i], hp, step)
+                want_sum += int(ref[i][3].view(np.int16).astype(np.int64).sum())
+            assert int(after.item()) == want_sum and int(after.item()) != int(before.item()), f"step {step}"
+            assert st.params_cpu == sizes[0] + sizes[2] and st.params_gpu == sizes[1] + sizes[3]
+        got_model = model.view(torch.int16).cpu().numpy().view(np.uint16)
+        for i, n in enumerate(sizes):
+            assert_parity(f"large direct model, subgroup {i}", (host[i]["p"], host[i]["m"], host[i]["v"]), ref[i][:3],
+                          got_model[offs[i]:offs[i] + n], ref[i][3])
+    finally:
+        ctx.close()
+        host = None
+        pin.free()
+
+
 @pytest.mark.parametrize("optimizer", ["adagrad", "rmsprop"])
 def test_other_rules_through_the_phase(optimizer, hp):
     """Adagrad and RMSProp: mixed plan with a resident, device and host gradients, pieces smaller than
@@ -307,11 +383,46 @@ def test_phase_allocates_no_device_memory(hp):
     assert free_after == free_before
 
 
-def test_calibration_reports_plausible_rates():
-    ctx = make_context(2, 4 << 20, host_threads=8, chunk_params=1 << 20, ring_chunks=16)
-    cm = ctx.dos_calibrate()
-    ctx.close()
+def _plausible(cm):
     assert 5e9 < cm.h2d_Bps < 130e9 and 5e9 < cm.d2h_Bps < 130e9
     assert 20e9 < cm.gpu_params_per_s < 400e9
     assert 0.05e9 < cm.cpu_params_per_s < 100e9
     assert 0 < cm.launch_overhead_s < 1e-3
+    assert cm.downscale_params_per_s == 0.0
+
+
+def test_calibration_reports_plausible_rates():
+    ctx = make_context(2, 4 << 20, host_threads=8, chunk_params=1 << 20, ring_chunks=16)
+    cm = ctx.dos_calibrate()
+    ctx.close()
+    ctx._keep[1].free()
+    _plausible(cm)
+
+
+def test_calibration_of_a_direct_context_without_a_ring(hp):
+    """A context whose host lane stores through the BAR needs no upload ring; its calibration measures the
+    host update through that same path (16-bit output into device memory) and the link with pinned memory
+    of its own, and leaves the context fit for phases."""
+    if not dos.dos_device_large_bar(0):
+        pytest.skip("the device memory is not mapped into the host's address space")
+    ctx = make_context(3, 4 << 20, host_threads=8, chunk_params=1 << 20, ring_chunks=0,
+                       flags=dos.DOS_CTX_UPLOAD_DIRECT)
+    st = OffloadedState([600_000, 300_008, 400_000], S.BASE_SEED + 70)
+    try:
+        cm = ctx.dos_calibrate()
+        _plausible(cm)
+        plan = dos.Plan.manual([0, 1, 0], None, 3, 4 << 20)
+        for step in (1, 2):
+            st.set_grads(step)
+            ctx.dos_run_update_phase(st.sgs, plan, dos.hparams(step=step, **hp))
+            st.oracle_step(hp, step)
+            st.check(f"after calibration, step {step}")
+    finally:
+        ctx.close()
+        st.free()
+    # no slot at all: nothing to measure the link or the kernel with
+    ctx = make_context(0, 1 << 16, 2, ring_chunks=0, flags=dos.DOS_CTX_UPLOAD_DIRECT)
+    with pytest.raises(dos.DosError) as e:
+        ctx.dos_calibrate()
+    assert e.value.status == dos.DOS_EBUDGET
+    ctx.close()

@@ -38,6 +38,19 @@ def test_update_phase_host_logic_under_sanitizers(name, flags, env, tmp_path):
     assert "phase_driver ok" in r.stdout
 
 
+def test_update_phase_allocates_no_host_memory(tmp_path):
+    """Section 4.1: the interleaved update must not pay for allocations.  The same driver with every
+    heap allocation of the process counted -- operator new replaced, malloc / calloc / realloc /
+    aligned_alloc / posix_memalign wrapped by the linker: the count must not move across any
+    dos_run_update_phase call, profiling statistics included (half of the driver's contexts profile)."""
+    exe = tmp_path / "phase_driver_allocs"
+    wraps = ["-Wl,--wrap=" + f for f in ("malloc", "calloc", "realloc", "aligned_alloc", "posix_memalign")]
+    subprocess.check_call([*COMMON, *STUB, "-DDOS_COUNT_ALLOCS", *PHASE_SOURCES, *wraps, "-o", str(exe)])
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
+    assert "phase_driver ok" in r.stdout
+
+
 @pytest.mark.parametrize("name,flags,env", [
     ("asan_ubsan", ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"],
      {"ASAN_OPTIONS": "detect_leaks=1:abort_on_error=0", "UBSAN_OPTIONS": "print_stacktrace=1"}),
