@@ -378,6 +378,35 @@ dos_status dos_ctx_last_timeline(const dos_ctx* ctx, float* ms6, int32_t max_pie
  * the two lanes, and falls back to the host cores alone where staging does not pay. */
 dos_status dos_cost_model_observe(dos_cost_model* cm, const dos_phase_stats* st);
 
+/* ---- for callers that cannot allocate -------------------------------------- */
+
+/* Largest subgroup dos_gpu_update_staged accepts, in parameters.  Its staging
+ * array holds 14 bytes per parameter (p, m, v and the gradient): 28 MiB on every
+ * GPU the library runs on, from the first use of the library there until the
+ * process ends. */
+#define DOS_STAGED_MAX_PARAMS 2097152
+
+/* The GPU lane of dos_run_update_phase for ONE subgroup whose p, m, v live in
+ * pinned host memory, with no context and no memory handed in: prefetch into the
+ * library's own staging array, fused update (hp->optimizer), flush back -- all
+ * enqueued on hip_stream (a hipStream_t, NULL = the default stream) and ordered by
+ * it alone; the call returns without waiting, and the result is the same, bit for
+ * bit, as that of dos_run_update_phase with this subgroup GPU-planned.
+ * For callers that cannot call hipMalloc -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation: this function calls no
+ * hipMalloc, hipFree or other allocating routine.  (Its first call on a device
+ * looks up the device address of the staging array; make that call outside any
+ * capture.)  sg->g is device memory (grad_loc DOS_DEVICE) or pinned host memory
+ * (staged with the state); sg->p_lp is device memory; sg->m may be NULL for
+ * Adagrad and RMSProp.  All calls on one GPU share that GPU's staging array, which
+ * keeps the last call's contents (every call overwrites what it reads): calls
+ * whose work overlaps in time on one GPU -- on different streams, or from
+ * different threads -- race; order them on one stream or with events.
+ * Errors: DOS_EINVAL, DOS_EALIGN, DOS_ESTATE (state not in pinned host memory),
+ * DOS_EBUDGET (sg->n > DOS_STAGED_MAX_PARAMS: the subgroup does not fit the
+ * staging array; nothing has been touched), DOS_EHIP. */
+dos_status dos_gpu_update_staged(const dos_subgroup* sg, const dos_hparams* hp, void* hip_stream);
+
 /* ---- utilities ------------------------------------------------------------ */
 
 /* *yes = 1 when the whole memory of HIP device `device` is mapped into the host's

@@ -11,6 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdos.so")
 
 DOS_OK, DOS_EINVAL, DOS_EALIGN, DOS_EBUDGET, DOS_EHIP, DOS_ESTATE, DOS_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+DOS_STAGED_MAX_PARAMS = 2097152
 DOS_HOST_PINNED, DOS_DEVICE, DOS_HOST_PAGEABLE = 0, 1, 2
 DOS_ON_CPU, DOS_ON_GPU = 0, 1
 DOS_OPT_ADAMW, DOS_OPT_ADAGRAD, DOS_OPT_RMSPROP = 0, 1, 2
@@ -98,6 +99,7 @@ SIGNATURES = {
     "dos_device_large_bar": (C.c_int, [C.c_int32, C.POINTER(C.c_int32)]),
     "dos_pinned_alloc": (C.c_int, [C.POINTER(C.c_void_p), C.c_uint64]),
     "dos_pinned_free": (C.c_int, [C.c_void_p]),
+    "dos_gpu_update_staged": (C.c_int, [C.POINTER(dos_subgroup), C.POINTER(dos_hparams), C.c_void_p]),
     "dos_host_advise_hugepages": (C.c_int, [C.c_void_p, C.c_uint64]),
     "dos_host_prefault": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32]),
     "dos_strerror": (C.c_char_p, [C.c_int]),
@@ -274,6 +276,10 @@ def dos_pinned_alloc(nbytes: int) -> int:
 
 def dos_pinned_free(ptr: int) -> None:
     check(load().dos_pinned_free(C.c_void_p(ptr)), "dos_pinned_free")
+
+
+def dos_gpu_update_staged(sg: dos_subgroup, hp: dos_hparams, stream: int = 0) -> None:
+    check(load().dos_gpu_update_staged(C.byref(sg), C.byref(hp), C.c_void_p(stream)), "dos_gpu_update_staged")
 
 
 def dos_host_advise_hugepages(ptr: int, nbytes: int) -> bool:

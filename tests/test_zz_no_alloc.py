@@ -1,0 +1,94 @@
+"""dos_gpu_update_staged -- the GPU lane of the update phase for one host-resident subgroup through the
+library's own static staging array, for callers that cannot allocate -- against dos_run_update_phase on
+the same inputs: two calls in a row, the second with a smaller subgroup, and both against the oracle."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import dos_synth as S
+import paper_2410_21316_amd as dos
+
+from gpu_util import OffloadedState, make_context
+
+pytestmark = pytest.mark.gpu
+
+
+_CALLS = {"n": 0}
+
+
+def _pair(n, seed, grad_on_device):
+    """The same subgroup twice: `a` goes through dos_run_update_phase, `b` through the new entry point."""
+    a = OffloadedState([n], seed, grad_on_device=[grad_on_device])
+    b = OffloadedState([n], seed, grad_on_device=[grad_on_device])
+    return a, b
+
+
+@pytest.mark.parametrize("optimizer", ["adamw", "rmsprop"])
+def test_static_staging_matches_the_update_phase_on_two_calls_in_a_row(optimizer, hp):
+    ctx = make_context(2, 1 << 20, 2, ring_chunks=2)
+    plan = dos.Plan.manual([1], None, 2, 1 << 20)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):           # the runtime sets a stream up at its first use: not this library's doing
+        warm = torch.zeros(1024, device="cuda:0").add_(1)
+        warm_host = warm.to("cpu", non_blocking=True)
+    stream.synchronize()
+    del warm, warm_host
+    cases = [(1_500_003, True), (700_001, False)]           # the second call is smaller, and stages its gradient
+    pairs = [_pair(n, S.BASE_SEED + 80 + k, gd) for k, (n, gd) in enumerate(cases)]
+    try:
+        for step in (1, 2):
+            for (n, gd), (a, b) in zip(cases, pairs):
+                h = dos.hparams(step=step, optimizer=optimizer, **hp)
+                a.set_grads(step)
+                b.set_grads(step)
+                ctx.dos_run_update_phase(a.sgs, plan, h)              # (also loads this rule's kernel)
+                torch.cuda.synchronize()
+                free_before = torch.cuda.mem_get_info()[0]
+                dos.dos_gpu_update_staged(b.sgs[0], h, stream.cuda_stream)
+                stream.synchronize()
+                # no device memory is taken by a call (the process's first call maps the code object that
+                # holds the staging array: that one is set-up)
+                if _CALLS["n"] > 0:
+                    assert torch.cuda.mem_get_info()[0] == free_before
+                _CALLS["n"] += 1
+                a.oracle_step(hp, step, optimizer=optimizer)
+                b.oracle_step(hp, step, optimizer=optimizer)
+                for x, y in zip(a.current(0), b.current(0)):
+                    assert np.array_equal(np.asarray(x).view(np.uint32), np.asarray(y).view(np.uint32))
+                assert np.array_equal(a.lp(0), b.lp(0))
+                a.check(f"phase {optimizer} n={n} step {step}")
+                b.check(f"static staging {optimizer} n={n} step {step}")
+    finally:
+        ctx.close()
+        ctx._keep[1].free()
+        for a, b in pairs:
+            a.free()
+            b.free()
+
+
+def test_static_staging_rejects_what_does_not_fit_and_what_it_cannot_reach(hp):
+    lib = dos.load()
+    h = dos.hparams(step=1, **hp)
+    big = dos.subgroup(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, dos.DOS_STAGED_MAX_PARAMS + 1, dos.DOS_HOST_PINNED,
+                       dos.DOS_DEVICE)
+    assert lib.dos_gpu_update_staged(C.byref(big), C.byref(h), None) == dos.DOS_EBUDGET
+    st = OffloadedState([1000], S.BASE_SEED + 90, grad_on_device=[True])
+    try:
+        before = st.snapshot()
+        sg = st.sgs[0]
+        dev = dos.subgroup(sg.p, sg.m, sg.v, sg.g, sg.p_lp, sg.n, dos.DOS_DEVICE, dos.DOS_DEVICE)
+        assert lib.dos_gpu_update_staged(C.byref(dev), C.byref(h), None) == dos.DOS_ESTATE
+        bad = dos.hparams(**{**hp, "step": 0})
+        assert lib.dos_gpu_update_staged(C.byref(sg), C.byref(bad), None) == dos.DOS_EINVAL
+        odd = dos.subgroup(sg.p + 4, sg.m, sg.v, sg.g, sg.p_lp, sg.n - 8, dos.DOS_HOST_PINNED, dos.DOS_DEVICE)
+        assert lib.dos_gpu_update_staged(C.byref(odd), C.byref(h), None) == dos.DOS_EALIGN
+        empty = dos.subgroup(0, 0, 0, 0, 0, 0, dos.DOS_HOST_PINNED, dos.DOS_DEVICE)
+        assert lib.dos_gpu_update_staged(C.byref(empty), C.byref(h), None) == dos.DOS_OK
+        torch.cuda.synchronize()
+        for x, y in zip(before, st.snapshot()):
+            for u, w in zip(x, y):
+                assert np.array_equal(u, w)
+    finally:
+        st.free()
