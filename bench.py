@@ -9,11 +9,15 @@ workloads ride in the same line under "extra": the single 1Mi-parameter subgroup
 the 7B-parameter resident state (70 x 100M), the 13B-parameter host-offloaded
 state (130 x 100M, 40 GB GPU budget) run through dos_plan_subgroups +
 dos_run_update_phase (with the host lane's 16-bit output stored straight into
-device memory where the machine allows, and once more through the pinned ring),
-and Adagrad / RMSProp on the primary workload's shape.
+device memory where the machine allows; then the pinned part of it through the
+GPU lane alone, the whole once more through the pinned ring, and under six
+schedules), the corners of the subgroup-size x budget grid, and Adagrad /
+RMSProp on the primary workload's shape.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,rules|none] [--upload auto|direct|pull|dma]
-                    [--rule adamw|adagrad|rmsprop] [--host-threads T] [--ablation] [--sweep] [--full-size] [--ceilings]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,c5,rules|none] [--upload auto|direct|pull|dma]
+                    [--rule adamw|adagrad|rmsprop] [--schedule balanced|stride|all_cpu|all_gpu|fixed:N]
+                    [--c4-legs gpu_lane,ring,ablation|none] [--host-threads T] [--ablation] [--sweep] [--full-size]
+                    [--ceilings]
 """
 from __future__ import annotations
 
@@ -159,7 +163,9 @@ def bench_c2(args, dos, torch, np):
         "hbm_frac_of_peak": BYTES_PER_PARAM * value / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": profiled_traffic("adam_kernel_c2.md"),
-                     "kernel": "dos::adam_kernel (fused AdamW)", "bytes_per_launch": BYTES_PER_PARAM * sizes[0],
+                     "traffic_source": "profiles/adam_kernel_c2.md: FETCH_SIZE and WRITE_SIZE of rocprofv3 --pmc runs of "
+                                       "this command, scaled by a copy kernel of known size; not measured in this run",
+                     "kernel": "dos::adam_kernel_tile (fused AdamW)", "bytes_per_launch": BYTES_PER_PARAM * sizes[0],
                      "avg_launch_us": launch_s * 1e6},
     }
     if not args.no_cpu_baseline:
@@ -380,7 +386,9 @@ def bench_c3(args, dos, torch, np):
 def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp=12, cpu_only=None):
     """schedule: 'balanced' (this library's planner), 'stride' (Eq. 1 + Algorithm 1), 'all_cpu' (every update
     on the host cores, as a fully offloaded optimizer does), 'static' (a fixed set of residents that fits the
-    budget, everything else on the host cores: static hybrid placement without interleaving)."""
+    budget, everything else on the host cores: static hybrid placement without interleaving), 'all_gpu'
+    (every stageable subgroup through the GPU lane), 'fixed:<n>' (n stageable subgroups, evenly spread,
+    through the GPU lane -- a plan that does not move, for profiling)."""
     if schedule == "balanced":
         return dos.dos_plan_subgroups(cm, sizes, budget_bytes, dos.DOS_PLAN_BALANCED, residents_max, bpp, cpu_only)
     if schedule == "stride":
@@ -393,17 +401,113 @@ def make_plan(dos, schedule, cm, sizes, budget_bytes, residents_max, bpp=12, cpu
         res = base.residents
         return dos.Plan.manual([dos.DOS_ON_GPU if r else dos.DOS_ON_CPU for r in res], None, base.c.n_slots,
                                base.c.slot_params, res)
-    raise ValueError(schedule)
+    movable = [i for i in range(len(sizes)) if not (cpu_only and cpu_only[i])]
+    if schedule == "all_gpu":
+        chosen = set(movable)
+    elif schedule.startswith("fixed:"):
+        c = min(int(schedule.split(":")[1]), len(movable))
+        chosen = {movable[q] for q in range(len(movable)) if (q + 1) * c // len(movable) > q * c // len(movable)}
+    else:
+        raise ValueError(schedule)
+    return dos.Plan.manual([dos.DOS_ON_GPU if i in chosen else dos.DOS_ON_CPU for i in range(len(sizes))], None,
+                           base.c.n_slots, base.c.slot_params)
+
+
+class OracleShare:
+    """The oracle's share of a host-offloaded state: the first `take` of every 1,048,576 elements of every
+    subgroup (elements are independent, so the oracle is exact on its share).  It follows the state through
+    every phase that is run on it, whatever leg of the benchmark runs it."""
+
+    def __init__(self, state, torch, np, take=1 << 16):
+        from paper_2410_21316_amd import workloads as W
+        self.W, self.torch, self.np, self.take = W, torch, np, take
+        self.samp = [[W.sample_take(t, take=take).cpu().numpy().copy() for t in state.state(i)]
+                     + [np.zeros(W.sample_take(state.state(i)[0], take=take).numel(), np.uint16)]
+                     for i in range(len(state.sizes))]
+        self.touched = [False] * len(state.sizes)
+
+    def describe(self):
+        return f"first {self.take:,} of every 1,048,576 elements of every subgroup, every step"
+
+    def step(self, state, rule, step, hp_kw, only=None):
+        from oracle import adamw_oracle as ref
+        for i in (range(len(state.sizes)) if only is None else only):
+            gs = self.W.sample_take(state.g[i], take=self.take).view(self.torch.int16).cpu().numpy().view(self.np.uint16)
+            s = self.samp[i]
+            ref.optimizer_step(rule, s[0], s[1], s[2], gs, s[3], step=step, threads=0, **hp_kw)
+            self.touched[i] = True
+
+    def mismatches(self, state):
+        np = self.np
+        bad = 0
+        for i in range(len(state.sizes)):
+            for t, want in zip(state.state(i), self.samp[i][:3]):
+                got = self.W.sample_take(t, take=self.take).cpu().numpy()
+                bad += int(np.count_nonzero(got.view(np.uint32) != want.view(np.uint32)))
+            if self.touched[i]:                 # the 16-bit copy exists once the subgroup has been updated
+                got = self.W.sample_take(state.lp[i], take=self.take).view(self.torch.int16).cpu().numpy().view(np.uint16)
+                bad += int(np.count_nonzero(got != self.samp[i][3]))
+        return bad
+
+
+def host_stream_ceiling(dos, torch, np, host_threads, direct):
+    """Host-memory stream with the host update's access pattern and (almost) no arithmetic, in the same
+    run and with the same thread count: the ceiling the host lane is judged against.  Reads p, m, v, g and
+    rewrites p, m, v of a 64 Mi-parameter buffer (1.9 GB, far beyond the caches); the 16-bit output goes
+    through the PCIe BAR into device memory (direct uploads) or into host memory (ring uploads)."""
+    from paper_2410_21316_amd import probe
+    n = 64 << 20
+    arrs = [torch.empty(n, dtype=torch.float32) for _ in range(3)] + [torch.empty(n, dtype=torch.int16)]
+    for t in arrs:
+        dos.dos_host_prefault(t.data_ptr(), t.numel() * t.element_size(), host_threads)
+        t.zero_()
+    if direct:
+        out = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+        torch.cuda.synchronize()
+        dos.dos_host_prefault(out.data_ptr(), n * 2, host_threads)      # map the device pages for the host
+    else:
+        out = torch.zeros(n, dtype=torch.int16)
+    ptrs = [t.data_ptr() for t in arrs]
+    bpp = 26 if direct else 28
+    by_threads = {}
+    for T in sorted({max(1, host_threads // 2), max(1, host_threads * 3 // 4), host_threads}):
+        probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, n, T, 1, direct)                   # warm-up
+        best = min(probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, n, T, 3, direct) / 3 for _ in range(3))
+        by_threads[T] = bpp * n / best / 1e9
+    top = max(by_threads, key=by_threads.get)
+    return {"GBps": by_threads[top], "threads_at_best": top, "GBps_by_threads": by_threads, "bytes_per_param": bpp,
+            "what": "plain stream of the host update's access pattern (read p, m, v, g; rewrite p, m, v; 16-bit output "
+                    + ("stored through the PCIe BAR" if direct else "to host memory") + "), 64 Mi parameters, best of "
+                    "3 x 3 sweeps per thread count, same run"}
+
+
+def calibrate_peaks(ctx, log, tag, rule):
+    """dos_calibrate twice; each rate keeps the better of the two (they are peaks: bounds are priced with them)."""
+    cms = [ctx.dos_calibrate() for _ in range(2)]
+    cm = cms[0]
+    for f in ("h2d_Bps", "d2h_Bps", "gpu_params_per_s", "cpu_params_per_s"):
+        setattr(cm, f, max(getattr(c, f) for c in cms))
+    cm.launch_overhead_s = min(c.launch_overhead_s for c in cms)
+    cm.fp32_arrays = 3 if rule == "adamw" else 2    # Adagrad, RMSProp stage p and v only
+    log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
+        f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (stand-alone, through the "
+        f"upload path in use)")
+    return cm
 
 
 def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_threads, gkw, seed, check=True,
                     cm=None, residents_max=0, tag="c4", state=None, adapt=True, schedule="balanced",
-                    fresh_grads=True, spill_grads=False, pageable_rest=False, rule="adamw", upload_flags=None):
+                    fresh_grads=True, spill_grads=False, pageable_rest=False, rule="adamw", upload_flags=None,
+                    share=None, only=None, keep_steps=True, peaks=None):
     """Plan + run the interleaved phase on a host-offloaded state; returns a dict.
-    fresh_grads=False generates the gradients once and reuses them for every step;
+    fresh_grads=False generates the gradients once and reuses them for every step, fresh_grads="keep" uses
+    the gradients the state already holds (the caller generated them);
     spill_grads=True keeps every gradient in pinned host memory (GPU-planned subgroups fetch theirs
     with p, m, v through 14-byte slots); pageable_rest=True keeps the subgroups the machine cannot pin in
-    ordinary host memory (CPU-only) instead of dropping them."""
+    ordinary host memory (CPU-only) instead of dropping them; `only` restricts the phase to a subset of the
+    subgroups (the others are not part of the phase at all); `share` is the oracle's share of the state;
+    `peaks` are the calibrated stand-alone rates that price the bounds when `cm` is a cost model that earlier
+    phases have already adapted."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     hp_kw = dict(S.HPARAMS)
@@ -422,11 +526,16 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
                 f"limit); the other {len(sizes) - state.n_pinned} live in pageable host memory and stay on the host cores")
         sizes = list(state.sizes)
         log(f"[{tag}] built {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
-    if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT and own_state:
-        t0 = time.perf_counter()
-        state.map_model_for_host_writes(host_threads)
-        log(f"[{tag}] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
-    cpu_only = state.cpu_only if any(state.cpu_only) else None
+        if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT:
+            t0 = time.perf_counter()
+            state.map_model_for_host_writes(host_threads)
+            log(f"[{tag}] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
+    all_sizes = list(state.sizes)
+    members = list(range(len(all_sizes))) if only is None else list(only)
+    sizes = [all_sizes[i] for i in members]
+    cpu_only_all = state.cpu_only
+    cpu_only = [cpu_only_all[i] for i in members]
+    cpu_only = cpu_only if any(cpu_only) else None
     # slots first (they decide what the context can do), then calibration, then the plan
     probe_cm = cm or dos.cost_model(50e9, 50e9, 180e9, 5e9)
     bpp = 14 if spill_grads else 12
@@ -434,99 +543,128 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
     ctx = W.make_context(plan.c.n_slots, plan.c.slot_params, host_threads, flags=dos.DOS_CTX_PROFILE | upload_flags,
                          stage_grads=spill_grads)
     if cm is None:
-        cm = ctx.dos_calibrate()
-        cm.fp32_arrays = 3 if rule == "adamw" else 2    # Adagrad, RMSProp stage p and v only
-        log(f"[{tag}] calibrated: H2D {cm.h2d_Bps/1e9:.1f} GB/s, D2H {cm.d2h_Bps/1e9:.1f} GB/s (duplex), "
-            f"U_g {cm.gpu_params_per_s/1e9:.1f} G/s, U_c {cm.cpu_params_per_s/1e9:.2f} G/s (stand-alone)")
-    link = (cm.h2d_Bps, cm.d2h_Bps)
-    calibrated = (cm.h2d_Bps, cm.d2h_Bps, cm.gpu_params_per_s, cm.cpu_params_per_s, cm.downscale_params_per_s,
-                  cm.launch_overhead_s)
+        cm = calibrate_peaks(ctx, log, tag, rule)
+    calibrated = tuple(peaks) if peaks else (cm.h2d_Bps, cm.d2h_Bps, cm.gpu_params_per_s, cm.cpu_params_per_s,
+                                             cm.downscale_params_per_s, cm.launch_overhead_s)
+    link = (calibrated[0], calibrated[1])
     results = []
-    samp = None
-    if check:
-        from oracle import adamw_oracle as ref
-        idxs = [torch.from_numpy(W.sample_index(n)) for n in sizes]
-
-        def take(t, idx):
-            return (t[idx.to(t.device)].cpu() if t.is_cuda else t[idx]).numpy().copy()
-
-        # the oracle's share starts from the state as it is now (wherever it lives)
-        samp = [[take(t, idxs[i]) for t in state.state(i)] + [np.zeros(idxs[i].numel(), np.uint16)]
-                for i in range(len(sizes))]
+    if check and share is None:
+        share = OracleShare(state, torch, np)
+    sb = 12.0 if rule == "adamw" else 8.0
     for step in range(1, warmup + steps + 1):
         # with feedback on, the first warm-up phase runs on the host cores alone: together with the staged
         # phases that follow it tells the cost model what staging takes away from the host lane
         probe_all_cpu = adapt and schedule == "balanced" and step == 1 and warmup >= 2 and not residents_max
         plan = make_plan(dos, "all_cpu" if probe_all_cpu else schedule, cm, sizes, budget_bytes, residents_max, bpp,
                          cpu_only)
-        state.place(plan.targets, plan.residents, spill_all_grads=spill_grads)
-        if fresh_grads or step == 1:
+        # the plan covers the members; everybody else keeps its place and takes no part
+        tg_all, res_all = [dos.DOS_ON_CPU] * len(all_sizes), [0] * len(all_sizes)
+        for k, i in enumerate(members):
+            tg_all[i], res_all[i] = plan.targets[k], plan.residents[k]
+        state.place(tg_all, res_all, spill_all_grads=spill_grads)
+        if fresh_grads is True or (step == 1 and fresh_grads != "keep"):
             state.fill_grads(step, **gkw)
         state.sync_host_grads()
-        st = ctx.dos_run_update_phase(state.sgs, plan, dos.hparams(step=step, optimizer=rule, **hp_kw))
+        sgs = state.sgs if only is None else (dos.dos_subgroup * len(members))(*[state.sgs[i] for i in members])
+        st = ctx.dos_run_update_phase(sgs, plan, dos.hparams(step=step, optimizer=rule, **hp_kw))
         lb_plan = max(st.h2d_bytes / link[0], st.d2h_bytes / link[1])
+        lb_nominal = max(st.h2d_bytes, st.d2h_bytes) / (LINK_NOMINAL_GBPS * 1e9)
+        staged = sb * st.params_gpu
         r = {"step": step, "wall_s": st.wall_s, "n_gpu": st.n_gpu, "n_cpu": st.n_cpu, "n_resident": st.n_resident,
              "gpu_fraction": (st.params_gpu + st.params_resident) / max(1, sum(sizes)),
              "h2d_GBps": st.h2d_bytes / st.wall_s / 1e9, "d2h_GBps": st.d2h_bytes / st.wall_s / 1e9,
              "h2d_busy_s": st.h2d_busy_s, "d2h_busy_s": st.d2h_busy_s, "gpu_busy_s": st.gpu_busy_s,
+             "h2d_span_s": st.h2d_span_s, "d2h_span_s": st.d2h_span_s,
              "duplex_overlap_s": st.duplex_overlap_s, "cpu_lane_s": st.cpu_lane_s, "gpu_lane_s": st.gpu_lane_s,
              "host_update_params_per_s": st.params_cpu / st.cpu_lane_s if st.cpu_lane_s > 0 else None,
+             # host memory traffic of the phase: 26 B (28 through the ring) per host-updated parameter, and
+             # every staged byte is read from or written to host memory once
+             "host_dram_GBps": ((26.0 if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT else 28.0) * st.params_cpu
+                                + 2.0 * staged) / st.wall_s / 1e9,
              "lower_bound_s": lb_plan, "ratio_to_lower_bound": st.wall_s / lb_plan if lb_plan > 0 else None,
+             "ratio_to_nominal_link_bound": st.wall_s / lb_nominal if lb_nominal > 0 else None,
              "predicted_s": plan.c.predicted_s, "timed": step > warmup}
+        if st.params_gpu and st.h2d_busy_s > 0:
+            # where the GPU lane's time went: the prefetches at the calibrated rate, what they lost to the
+            # uploads and the host update sharing the direction and the host's memory, the gaps between
+            # copies, and the tail behind the last prefetch (its kernel and flush)
+            ideal = staged / link[0]
+            uploads = 2.0 * st.params_cpu
+            share_busy = min(1.0, st.h2d_busy_s / st.cpu_lane_s) if st.cpu_lane_s > 0 else 0.0
+            combined = (staged + uploads * share_busy) / st.h2d_busy_s          # uploads are spread over the host lane
+            r["gpu_lane_accounting"] = {
+                "h2d_combined_rate_while_prefetches_busy_GBps": combined / 1e9,
+                "link_bound_of_plan_s": lb_plan,
+                "excess_over_link_bound_s": st.wall_s - lb_plan,
+                "excess_from_link_rate_shortfall_s": (st.h2d_bytes / combined - st.h2d_bytes / link[0])
+                                                     if st.h2d_bytes / link[0] >= st.d2h_bytes / link[1] else None,
+                "prefetches_at_calibrated_rate_s": ideal, "prefetch_slowdown_s": st.h2d_busy_s - ideal,
+                "h2d_idle_between_copies_s": st.h2d_span_s - st.h2d_busy_s,
+                "d2h_idle_between_copies_s": st.d2h_span_s - st.d2h_busy_s,
+                "lead_and_tail_s": st.gpu_lane_s - st.h2d_span_s,
+                "sum_s": ideal + (st.h2d_busy_s - ideal) + (st.h2d_span_s - st.h2d_busy_s)
+                         + (st.gpu_lane_s - st.h2d_span_s),
+                "gpu_lane_s": st.gpu_lane_s,
+                "h2d_rate_while_busy_GBps": staged / st.h2d_busy_s / 1e9,
+                "d2h_rate_while_busy_GBps": staged / st.d2h_busy_s / 1e9 if st.d2h_busy_s > 0 else None,
+                "uploads_share_of_h2d_bytes": 2.0 * st.params_cpu / st.h2d_bytes if st.h2d_bytes else 0.0}
         results.append(r)
         log(f"[{tag}] step {step}: {st.wall_s:.3f}s gpu {st.n_gpu}+{st.n_resident}r cpu {st.n_cpu} "
-            f"lanes cpu {st.cpu_lane_s:.3f} gpu {st.gpu_lane_s:.3f} LB {lb_plan:.3f} ratio {r['ratio_to_lower_bound']}")
+            f"lanes cpu {st.cpu_lane_s:.3f} gpu {st.gpu_lane_s:.3f} LB {lb_plan:.3f} ratio "
+            f"{r['ratio_to_lower_bound'] if r['ratio_to_lower_bound'] is None else round(r['ratio_to_lower_bound'], 3)}")
         if adapt:
             # feed the measured lane rates back into the cost model (the plan is
             # re-derived every iteration, as a training loop would)
             dos.dos_cost_model_observe(cm, st)
         if check:
-            for i in range(len(sizes)):
-                gs = state.g[i][idxs[i].to("cuda:0")].view(torch.int16).cpu().numpy().view(np.uint16)
-                ref.optimizer_step(rule, samp[i][0], samp[i][1], samp[i][2], gs, samp[i][3], step=step, threads=0,
-                                   **hp_kw)
-    mism = None
-    if check:
-        mism = 0
-        for i in range(len(sizes)):
-            cur = state.state(i)
-            for t, host_a in zip(cur, samp[i][:3]):
-                got = t[idxs[i].to(t.device)].cpu().numpy() if t.is_cuda else t[idxs[i]].numpy()
-                mism += int(np.count_nonzero(got.view(np.uint32) != host_a.view(np.uint32)))
-            got = state.lp[i][idxs[i].to("cuda:0")].view(torch.int16).cpu().numpy().view(np.uint16)
-            mism += int(np.count_nonzero(got != samp[i][3]))
+            share.step(state, rule, step, hp_kw, only=members)
+    mism = share.mismatches(state) if check else None
     timed = [r for r in results if r["timed"]]
     best = min(timed, key=lambda r: r["wall_s"])
     mean_wall = sum(r["wall_s"] for r in timed) / len(timed)
-    sb = 12.0 if rule == "adamw" else 8.0
     res_params = sum(n for n, r in zip(sizes, plan.residents or [0] * len(sizes)) if r)
-    movable = [not c and not r for c, r in zip(state.cpu_only, plan.residents or [0] * len(sizes))]
-    lb_opt, k_opt = lower_bound_opt(sizes, movable, link, calibrated[2], calibrated[3], sb, res_params)
+    pinned_ok = [not c for c in (cpu_only or [0] * len(sizes))]
+    movable = [ok and not r for ok, r in zip(pinned_ok, plan.residents or [0] * len(sizes))]
+    # a bound must be priced with peaks: where a phase beat a calibrated rate, the phase's own rate is the peak
+    seen_u_cpu = max([r["host_update_params_per_s"] or 0.0 for r in results])
+    u_cpu_peak = max(calibrated[3], seen_u_cpu)
+    lb_opt, k_opt = lower_bound_opt(sizes, movable, link, calibrated[2], u_cpu_peak, sb, res_params)
     lb_free, k_free = lower_bound_opt(sizes, [not r for r in (plan.residents or [0] * len(sizes))], link,
-                                      calibrated[2], calibrated[3], sb, res_params)
+                                      calibrated[2], u_cpu_peak, sb, res_params)
     out = {"update_phase_s_per_iter": mean_wall, "best_s": best["wall_s"],
            "lower_bound_opt_s": lb_opt, "lower_bound_opt_gpu_subgroups": k_opt,
            "ratio_to_lower_bound_opt": mean_wall / lb_opt,
            "lower_bound_opt_all_pinnable_s": lb_free, "ratio_to_lower_bound_opt_all_pinnable": mean_wall / lb_free,
            "lower_bound_note": "ratio_to_lower_bound prices the executed plan's link bytes at the measured duplex "
                                "link rates; lower_bound_opt is the best any split could reach with link, host "
-                               "update and GPU update all at their calibrated stand-alone peaks (over the "
-                               "subgroups this machine can pin; _all_pinnable: if it could pin all of them)",
-           "params": sum(sizes), "n_subgroups": len(sizes), "n_subgroups_pinned": state.n_pinned,
+                               "update and GPU update all at their stand-alone peaks (the calibrated rates, or a "
+                               "phase's own rate where it beat them; over the subgroups this machine can pin; "
+                               "_all_pinnable: if it could pin all of them)",
+           "host_rate_peak_used_for_bounds": u_cpu_peak, "host_rate_calibrated": calibrated[3],
+           "host_rate_best_phase": seen_u_cpu, "phase_beat_calibrated_host_rate": seen_u_cpu > calibrated[3],
+           "params": sum(sizes), "n_subgroups": len(sizes), "n_subgroups_pinned": sum(pinned_ok),
            "params_per_s": sum(sizes) / mean_wall,
            "ratio_to_lower_bound": sum(r["ratio_to_lower_bound"] for r in timed) / len(timed),
+           "ratio_to_nominal_link_bound": sum(r["ratio_to_nominal_link_bound"] for r in timed) / len(timed),
            "link_duplex_GBps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9, "nominal": LINK_NOMINAL_GBPS},
            "h2d_GBps": best["h2d_GBps"], "d2h_GBps": best["d2h_GBps"],
            "h2d_frac_of_measured_link": best["h2d_GBps"] * 1e9 / link[0],
            "d2h_frac_of_measured_link": best["d2h_GBps"] * 1e9 / link[1],
            "host_update_params_per_s": best["host_update_params_per_s"],
+           "host_dram_GBps": best["host_dram_GBps"],
            "gpu_fraction": best["gpu_fraction"], "n_slots": plan.c.n_slots, "slot_params": plan.c.slot_params,
            "host_threads": host_threads, "uploads": {0: "pull", 2: "dma", 8: "direct"}[upload_flags],
-           "sample_mismatches_vs_oracle": mism, "steps": results,
+           "sample_mismatches_vs_oracle": mism, "oracle_sample": share.describe() if check else None,
            "calibrated": calibrated}
+    out["_cost_model"] = cm                      # as adapted by the phases of this leg (not JSON: popped by callers)
+    if "gpu_lane_accounting" in best:
+        out["gpu_lane_accounting"] = best["gpu_lane_accounting"]
+    if keep_steps:
+        out["steps"] = results
     ctx.close()
     ctx._keep[1].free()          # the pinned upload ring
     if own_state:
+        state.place([dos.DOS_ON_CPU] * len(all_sizes), [0] * len(all_sizes))
         state.free()
     return out
 
@@ -552,47 +690,140 @@ def lower_bound_opt(sizes, movable, link, u_gpu, u_cpu, state_bytes, resident_pa
     return best
 
 
+ABLATION_ROWS = (
+    ("all updates on host cores (fully offloaded optimizer)", "all_cpu", 0, False),
+    ("static residents only (fixed hybrid placement)", "static", 1, False),
+    ("stride from Eq. 1 + Algorithm 1 placement", "stride", 0, False),
+    ("balanced plan with feedback (default)", "balanced", 0, False),
+    ("balanced plan, all gradients spilled to the host and fetched with the state", "balanced", 0, True),
+    ("balanced plan + static residents placed last", "balanced", 1, False))
+
+
+def schedule_ablation(args, dos, torch, np, state, share, budget, warmup, steps, tag="abl", calibrated=None,
+                      grads=False):
+    """The same host-offloaded state under different schedules, all through dos_run_update_phase: the
+    schedules the paper compares against are degenerate plans of the same pipeline."""
+    sizes = list(state.sizes)
+    rows = []
+    for name, schedule, res, spill in ABLATION_ROWS:
+        r = run_interleaved(dos, torch, np, sizes, budget, steps=steps, warmup=warmup, host_threads=args.host_threads,
+                            gkw={}, seed=None, check=share is not None, share=share,
+                            tag=f"{tag} " + schedule + ("+res" if res else "") + ("+spill" if spill else ""),
+                            state=state, residents_max=len(sizes) if res else 0, schedule=schedule, spill_grads=spill,
+                            fresh_grads=grads, cm=dos.cost_model(*calibrated) if calibrated else None)
+        r.pop("_cost_model", None)
+        last = r.pop("steps")[-1]
+        rows.append({"schedule": name, "s_per_iter": r["update_phase_s_per_iter"], "best_s": r["best_s"],
+                     "params_per_s": r["params_per_s"], "n_gpu": last["n_gpu"], "n_cpu": last["n_cpu"],
+                     "n_resident": last["n_resident"], "ratio_to_lower_bound": r["ratio_to_lower_bound"],
+                     "host_dram_GBps": r["host_dram_GBps"],
+                     "sample_mismatches_vs_oracle": r["sample_mismatches_vs_oracle"]})
+    base = rows[0]["s_per_iter"]
+    for r in rows:
+        r["speedup_vs_all_cpu"] = base / r["s_per_iter"]
+    return rows
+
+
 def bench_c4(args, dos, torch, np):
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     sizes = [100_000_000] * 130
+    legs = set(args.c4_legs.split(","))
     t0 = time.perf_counter()
     state = W.OffloadedState(sizes, S.BASE_SEED + 4, "cuda:0", pinned_reserve_bytes=1 << 30, pageable_rest=True)
     if state.n_pinned < len(sizes):
         log(f"[c4] this machine pins only {state.n_pinned} of the {len(sizes)} subgroups (hipHostMalloc limit); the "
             f"other {len(sizes) - state.n_pinned} live in pageable host memory and stay on the host cores")
     log(f"[c4] built {sum(sizes)*12/1e9:.0f} GB of host state in {time.perf_counter()-t0:.1f}s")
-    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+    direct = bool(UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT)
+    if direct:
         t0 = time.perf_counter()
         state.map_model_for_host_writes(args.host_threads)
         log(f"[c4] mapped the 16-bit model ({sum(sizes)*2/1e9:.0f} GB) for host writes in {time.perf_counter()-t0:.1f}s")
-    out = run_interleaved(dos, torch, np, sizes, 40 * 10**9, steps=5, warmup=3, host_threads=args.host_threads,
-                          gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4", state=state, rule=args.rule)
+    share = OracleShare(state, torch, np)
+    budget = 40 * 10**9
+    out = run_interleaved(dos, torch, np, sizes, budget, steps=5, warmup=3, host_threads=args.host_threads,
+                          gkw={}, seed=S.BASE_SEED + 4, check=True, share=share, tag="c4", state=state, rule=args.rule,
+                          schedule=args.schedule, adapt=args.schedule == "balanced")
     out["workload"] = ("c4: 13B params, fp32 p/m/v (156 GB) in host memory, 130 subgroups of 100,000,000, "
-                       "40 GB GPU budget, balanced plan re-derived per iteration; bf16 grads ~N(0,1e-3); 5 steps")
+                       "40 GB GPU budget, " + ("balanced plan re-derived per iteration" if args.schedule == "balanced"
+                                               else f"schedule {args.schedule}")
+                       + "; bf16 grads ~N(0,1e-3); 5 steps")
     if args.rule != "adamw":
         out["workload"] += f"; update rule {args.rule}: only p and v are updated and staged (8 B/param each way)"
     if out["n_subgroups_pinned"] < out["n_subgroups"]:
         out["workload"] += (f"; hipHostMalloc pins only {out['n_subgroups_pinned']} subgroups on this machine, the "
                             "others are in pageable host memory and are planned CPU-only")
-    if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
+    # the roofline that governs the executed plan when it keeps (most of) the work on the host cores:
+    # host memory bandwidth, against a plain stream of the same access pattern measured in this run
+    ceil = host_stream_ceiling(dos, torch, np, args.host_threads, direct)
+    bpp_host = 26.0 if direct else 28.0
+    same_kernel = out["host_rate_calibrated"] * bpp_host / 1e9
+    ceiling = max(ceil["GBps"], same_kernel)
+    out["host_dram"] = {"bound": "host memory bandwidth", "achieved_GBps": out["host_dram_GBps"],
+                        "ceiling_GBps": ceiling, "frac": out["host_dram_GBps"] / ceiling,
+                        "ceiling_plain_stream": ceil,
+                        "ceiling_same_kernel_standalone_GBps": same_kernel,
+                        "ceiling_note": "the higher of two same-run measurements: a plain stream of the same access "
+                                        "pattern, and the host update itself with all threads over a 1.9 GB buffer "
+                                        "(dos_calibrate); the arithmetic of the update paces its memory requests, and on "
+                                        "this host that reaches more bandwidth than the plain stream does",
+                        "traffic_model": "26 B per host-updated parameter with direct uploads (reads 4+4+4+2, writes "
+                                         "4+4+4; the 16-bit output leaves through the BAR), 28 B through the ring; "
+                                         "24 B per staged parameter (read by the prefetch, written by the flush)"}
+    log(f"[c4] host memory: phase {out['host_dram_GBps']:.0f} GB/s; ceilings: plain stream {ceil['GBps']:.0f} GB/s "
+        f"({ceil['threads_at_best']} threads), the update itself stand-alone {same_kernel:.0f} GB/s")
+    out.pop("_cost_model", None)
+    cm_cal = dos.cost_model(*out["calibrated"])
+    if "gpu_lane" in legs:
+        # The staging pipeline by itself: every subgroup this machine can pin goes through the GPU lane
+        # (prefetch, kernel, flush; Section 4.1's full-duplex overlap), the host lane has nothing to do.
+        pinned = [i for i in range(len(sizes)) if not state.cpu_only[i]]
+        lane = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=1, host_threads=args.host_threads,
+                               gkw={}, seed=None, check=True, share=share, tag="c4 gpu lane only", state=state,
+                               rule=args.rule, schedule="all_gpu", adapt=False, only=pinned, fresh_grads="keep",
+                               cm=dos.cost_model(*out["calibrated"]))
+        best = min((r for r in lane["steps"] if r["timed"]), key=lambda r: r["wall_s"])
+        out_lane = {k: lane[k] for k in (
+            "update_phase_s_per_iter", "best_s", "params", "n_subgroups", "params_per_s", "ratio_to_lower_bound",
+            "ratio_to_nominal_link_bound", "link_duplex_GBps", "h2d_GBps", "d2h_GBps", "h2d_frac_of_measured_link",
+            "d2h_frac_of_measured_link", "n_slots", "slot_params", "sample_mismatches_vs_oracle")}
+        out_lane["workload"] = (f"the {len(pinned)} subgroups of c4 that this machine can pin, all GPU-planned: "
+                                "prefetch, fused kernel and flush of 16 Mi-parameter pieces through 3 slots; host "
+                                "lane idle; 1 warm-up + 3 timed phases")
+        out_lane["duplex_overlap_frac_of_phase"] = best["duplex_overlap_s"] / best["wall_s"]
+        out_lane["gpu_kernel_busy_s"] = best["gpu_busy_s"]
+        out_lane["gpu_lane_accounting"] = best.get("gpu_lane_accounting")
+        out_lane["steps"] = [{k: r[k] for k in ("wall_s", "h2d_GBps", "d2h_GBps", "ratio_to_lower_bound",
+                                                "duplex_overlap_s", "h2d_busy_s", "d2h_busy_s", "h2d_span_s",
+                                                "d2h_span_s", "timed")} for r in lane["steps"]]
+        out["gpu_lane_only"] = out_lane
+    if direct and "ring" in legs:
         # The same state with the 16-bit parameters going through the pinned ring and the copy kernel: the
         # configuration in which this host leaves something for the link to do, i.e. the staged, link-bound
         # regime the interleaving is made for.
-        ring = run_interleaved(dos, torch, np, sizes, 40 * 10**9, steps=3, warmup=3, host_threads=args.host_threads,
-                               gkw={}, seed=S.BASE_SEED + 4, check=True, tag="c4 ring uploads", state=state,
-                               rule=args.rule, upload_flags=0)
+        ring = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=3, host_threads=args.host_threads,
+                               gkw={}, seed=S.BASE_SEED + 4, check=True, share=share, tag="c4 ring uploads",
+                               state=state, rule=args.rule, upload_flags=0, fresh_grads="keep")
         out["with_ring_uploads"] = {k: ring[k] for k in (
             "update_phase_s_per_iter", "best_s", "params_per_s", "ratio_to_lower_bound", "ratio_to_lower_bound_opt",
             "h2d_GBps", "d2h_GBps", "h2d_frac_of_measured_link", "d2h_frac_of_measured_link", "gpu_fraction",
-            "uploads", "sample_mismatches_vs_oracle")}
+            "host_dram_GBps", "uploads", "sample_mismatches_vs_oracle") if k in ring}
+        out["with_ring_uploads"]["gpu_lane_accounting"] = ring.get("gpu_lane_accounting")
+    if "ablation" in legs:
+        rows = schedule_ablation(args, dos, torch, np, state, share, budget, warmup=2, steps=3,
+                                 calibrated=out["calibrated"], grads="keep")
+        out["schedule_ablation"] = {
+            "workload": "the c4 state under six schedules, all through dos_run_update_phase; gradients generated "
+                        "once; 2 warm-up + 3 timed phases each; residents are moved to the device before timing",
+            "rows": rows}
     state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))
     state.free()
     return out
 
 
 def bench_ablation(args, dos, torch, np):
-    """The same host-offloaded state under different schedules, all through dos_run_update_phase."""
+    """The schedule table on its own state, plus the host-threads sweep (the paper's CPU-cores-per-GPU study)."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     sizes = [100_000_000] * 130
@@ -603,25 +834,8 @@ def bench_ablation(args, dos, torch, np):
     sizes = list(state.sizes)
     scale = sum(sizes) / 13e9
     budget = int(40 * 10**9 * scale)
-    rows = []
-    for name, schedule, res, spill in (
-            ("all updates on host cores (fully offloaded optimizer)", "all_cpu", 0, False),
-            ("static residents only (fixed hybrid placement)", "static", len(sizes), False),
-            ("stride from Eq. 1 + Algorithm 1 placement", "stride", 0, False),
-            ("balanced plan with feedback (default)", "balanced", 0, False),
-            ("balanced plan, all gradients spilled to the host and fetched with the state", "balanced", 0, True),
-            ("balanced plan + static residents placed last", "balanced", len(sizes), False)):
-        r = run_interleaved(dos, torch, np, sizes, budget, steps=4, warmup=3, host_threads=args.host_threads, gkw={},
-                            seed=S.BASE_SEED + 4, check=True,
-                            tag="abl " + schedule + ("+res" if res else "") + ("+spill" if spill else ""),
-                            state=state, residents_max=res, schedule=schedule, spill_grads=spill)
-        last = r.pop("steps")[-1]
-        rows.append({"schedule": name, "s_per_iter": r["update_phase_s_per_iter"], "best_s": r["best_s"],
-                     "params_per_s": r["params_per_s"], "n_gpu": last["n_gpu"], "n_cpu": last["n_cpu"],
-                     "n_resident": last["n_resident"], "sample_mismatches_vs_oracle": r["sample_mismatches_vs_oracle"]})
-    base = rows[0]["s_per_iter"]
-    for r in rows:
-        r["speedup_vs_all_cpu"] = base / r["s_per_iter"]
+    share = OracleShare(state, torch, np)
+    rows = schedule_ablation(args, dos, torch, np, state, share, budget, warmup=3, steps=4)
     # host cores per GPU (the paper's CPU-cores-per-GPU study, Section 5.4): fewer host threads make the
     # all-CPU schedule slower and the interleaved one comparatively better
     thread_rows = []
@@ -633,6 +847,7 @@ def bench_ablation(args, dos, torch, np):
             r = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=3, host_threads=T, gkw={},
                                 seed=S.BASE_SEED + 4, check=False, tag=f"threads {T} {schedule}", state=state,
                                 schedule=schedule, fresh_grads=False)
+            r.pop("_cost_model", None)
             pair[schedule] = r
         thread_rows.append({"host_threads": T, "all_cpu_s": pair["all_cpu"]["update_phase_s_per_iter"],
                             "balanced_s": pair["balanced"]["update_phase_s_per_iter"],
@@ -646,61 +861,68 @@ def bench_ablation(args, dos, torch, np):
             "rows": rows, "host_threads_sweep": thread_rows}
 
 
-def bench_c5(args, dos, torch, np):
+def bench_c5(args, dos, torch, np, sg_sizes_m, budgets_gb, full_size, steps=3, warmup=2, take=1 << 16):
     """Interleaving sweep: subgroup size x GPU budget, heavy-tailed gradients with 5 % zeros, 3 steps per cell.
     Each cell is run twice: state entirely host-resident (budget = staging only), and with the budget's
-    remainder used for static residents placed last."""
+    remainder used for static residents placed last.  One host state per subgroup size serves all its cells."""
     from paper_2410_21316_amd import workloads as W
     import dos_synth as S
     total_nominal = 13_000_000_000
     cells = []
     scale = None
-    for sg_params in [int(x) * 1_000_000 for x in args.sweep_sizes.split(",")]:
+    cm = peaks = None
+    for sg_params in [int(x) * 1_000_000 for x in sg_sizes_m]:
         n_sg = -(-total_nominal // sg_params)
         sizes = [sg_params] * (n_sg - 1) + [total_nominal - sg_params * (n_sg - 1)]
         if scale is not None and scale < 1:        # same parameter count for every subgroup size
             keep = int(round(scale * total_nominal))
             n_keep = max(1, keep // sg_params)
             sizes = [sg_params] * n_keep
+        t0 = time.perf_counter()
         state = W.OffloadedState(sizes, S.BASE_SEED + 5, "cuda:0", pinned_reserve_bytes=1 << 30,
-                                 pageable_rest=args.full_size)
+                                 pageable_rest=full_size)
         if UPLOAD_FLAGS & dos.DOS_CTX_UPLOAD_DIRECT:
             state.map_model_for_host_writes(args.host_threads)
         sizes = list(state.sizes)
+        log(f"[c5] S={sg_params//10**6}M: {len(sizes)} subgroups ({state.n_pinned} pinned) built in "
+            f"{time.perf_counter()-t0:.1f}s")
         if scale is None:
             scale = sum(sizes) / total_nominal
             if scale < 1:
                 log(f"[c5] this machine pins {sum(sizes)/1e9:.1f}B of the 13B parameters; budgets are scaled "
                     f"by {scale:.3f}")
-            else:
-                log(f"[c5] full size; {state.n_pinned} of {len(sizes)} subgroups pinned, the rest pageable (CPU-only)")
-        cm = None
-        for budget_gb in (8, 16, 32, 64):
+        share = OracleShare(state, torch, np, take=take)
+        state.fill_grads(1, heavy_tail=True, zero_pct=5.0)          # one set of gradients serves every cell
+        for budget_gb in budgets_gb:
             budget = int(budget_gb * 10**9 * scale)
             for residents in (0, len(sizes)):
                 tag = f"c5 S={sg_params//10**6}M B={budget_gb}GB{' +res' if residents else ''}"
                 try:
-                    r = run_interleaved(dos, torch, np, sizes, budget, steps=3, warmup=2,
-                                        host_threads=args.host_threads,
-                                        gkw=dict(heavy_tail=True, zero_pct=5.0), seed=S.BASE_SEED + 5,
-                                        check=True, tag=tag, state=state, residents_max=residents,
-                                        cm=(dos.cost_model(*cm) if cm else None), fresh_grads=False)
-                    if cm is None:
-                        cm = r.get("calibrated")
+                    # the first cell calibrates and lets the planner's feedback settle (3 warm-up phases); the
+                    # cost model it ends with is carried from cell to cell, as a training run carries it from
+                    # iteration to iteration
+                    r = run_interleaved(dos, torch, np, sizes, budget, steps=steps, warmup=warmup if cm else 3,
+                                        host_threads=args.host_threads, gkw={}, seed=S.BASE_SEED + 5,
+                                        check=True, share=share, tag=tag, state=state, residents_max=residents,
+                                        cm=cm, peaks=peaks, fresh_grads="keep", keep_steps=False)
+                    cm = r.pop("_cost_model")
+                    peaks = r["calibrated"]
                 except dos.DosError as e:
                     r = {"error": str(e)}
-                r.pop("steps", None)
-                r.pop("calibrated", None)
+                for k in ("calibrated", "lower_bound_note", "gpu_lane_accounting"):
+                    r.pop(k, None)
                 r.update({"subgroup_params": sg_params, "budget_GB_nominal": budget_gb,
                           "budget_bytes_scaled": budget, "static_residents": bool(residents)})
                 cells.append(r)
         state.place([dos.DOS_ON_CPU] * len(sizes), [0] * len(sizes))   # residents back to the host
         state.free()
-        del state
+        del state, share
         torch.cuda.empty_cache()
-    return {"workload": "c5: subgroup size {50,100,200,400}M x GPU budget {8,16,32,64} GB on host-resident state, "
-                        "grads Student-t(3) x 1e-3 with 5% zeros, 3 timed steps per cell; parameter count and "
-                        "budgets scaled by the fraction of 13B this machine can pin",
+    return {"workload": f"c5: subgroup size {{{','.join(str(x) for x in sg_sizes_m)}}}M x GPU budget "
+                        f"{{{','.join(str(b) for b in budgets_gb)}}} GB on 13B parameters of host-resident state "
+                        f"(what cannot be pinned is pageable and CPU-only), grads Student-t(3) x 1e-3 with 5% zeros, "
+                        f"generated once, {warmup} warm-up + {steps} timed steps per cell, each cell with and without "
+                        "static residents placed last",
             "scale": scale, "cells": cells}
 
 
@@ -709,9 +931,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--extra", default="c1,c3,c4,rules",
-                    help="comma list of extra workloads (c1, c3, c4, rules = Adagrad and RMSProp on the c2 shape) "
-                         "or 'none'")
+    ap.add_argument("--extra", default="c1,c3,c4,c5,rules",
+                    help="comma list of extra workloads (c1, c3, c4, c5 = the reduced subgroup-size x budget grid, "
+                         "rules = Adagrad and RMSProp on the c2 shape) or 'none'")
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--upload", default="auto", choices=["auto", "direct", "pull", "dma"],
                     help="how the host lane of the interleaved workloads sends the 16-bit parameters to the device: "
@@ -719,14 +941,22 @@ def main():
                          "into the host's address space), pull = copy kernel reading a pinned ring, dma = hipMemcpyAsync")
     ap.add_argument("--rule", default="adamw", choices=["adamw", "adagrad", "rmsprop"],
                     help="update rule of the interleaved workload c4 (the primary workload is always AdamW)")
+    ap.add_argument("--schedule", default="balanced",
+                    help="schedule of c4's main leg: balanced (planner with feedback), stride (Eq. 1), all_cpu, all_gpu, "
+                         "or fixed:<n> (n subgroups staged in every phase: a plan that does not move, for profiling "
+                         "the staged regime)")
+    ap.add_argument("--c4-legs", default="gpu_lane,ring,ablation",
+                    help="what c4 runs after its main leg: gpu_lane (the pinned subgroups through the GPU lane alone), "
+                         "ring (the main leg again with ring uploads), ablation (six schedules); 'none' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--ablation", action="store_true", help="also compare schedules on the host-offloaded state")
+    ap.add_argument("--ablation", action="store_true",
+                    help="the schedule table on a state of its own, longer, plus the host-threads sweep")
     ap.add_argument("--ceilings", action="store_true",
                     help="also measure the AdamW launch with only its loads / only its stores (HBM ceilings)")
-    ap.add_argument("--sweep", action="store_true", help="also run the c5 subgroup-size x budget sweep")
-    ap.add_argument("--sweep-sizes", default="50,100,200,400", help="subgroup sizes of the sweep, in millions")
+    ap.add_argument("--sweep", action="store_true", help="the full c5 grid (4 sizes x 4 budgets) instead of the reduced one")
+    ap.add_argument("--sweep-sizes", default="50,100,200,400", help="subgroup sizes of the full sweep, in millions")
     ap.add_argument("--full-size", action="store_true",
-                    help="ablation / sweep on the full 13B parameters: what cannot be pinned lives in pageable host "
+                    help="--ablation on the full 13B parameters: what cannot be pinned lives in pageable host "
                          "memory and is planned CPU-only (default: only the part that can be pinned)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (reference for traffic counters)")
@@ -750,6 +980,7 @@ def main():
     log(f"[bench] 16-bit uploads of the host lane: {upload}")
     if args.host_threads <= 0:
         args.host_threads = len(os.sched_getaffinity(0))
+    t_start = time.perf_counter()
     res = bench_c2(args, dos, torch, np)
     extra = {}
     wanted = [] if args.extra == "none" else [w.strip() for w in args.extra.split(",") if w.strip()]
@@ -757,18 +988,31 @@ def main():
         extra["c1_single_subgroup_1m"] = bench_c1(args, dos, torch, np)
     if "c3" in wanted:
         extra["c3_resident_7b"] = bench_c3(args, dos, torch, np)
-    if "c4" in wanted:
-        extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
     if "rules" in wanted:
         extra["other_update_rules"] = bench_other_rules(args, dos, torch, np)
     if args.ceilings:
         extra["hbm_stream_ceilings"] = bench_ceilings(args, dos, torch, np)
+    if "c4" in wanted:
+        log(f"[bench] {time.perf_counter()-t_start:.0f}s so far; c4")
+        extra["c4_interleaved_13b"] = bench_c4(args, dos, torch, np)
+        if "schedule_ablation" in extra["c4_interleaved_13b"]:
+            extra["schedule_ablation"] = extra["c4_interleaved_13b"].pop("schedule_ablation")
+        if "gpu_lane_only" in extra["c4_interleaved_13b"]:
+            extra["c4_gpu_lane_only"] = extra["c4_interleaved_13b"].pop("gpu_lane_only")
     if args.ablation:
-        extra["schedule_ablation"] = bench_ablation(args, dos, torch, np)
+        extra["schedule_ablation_long"] = bench_ablation(args, dos, torch, np)
     if args.sweep:
-        extra["c5_interleaving_sweep"] = bench_c5(args, dos, torch, np)
+        extra["c5_interleaving_sweep"] = bench_c5(args, dos, torch, np, args.sweep_sizes.split(","), (8, 16, 32, 64),
+                                                  full_size=True)
+    elif "c5" in wanted:
+        log(f"[bench] {time.perf_counter()-t_start:.0f}s so far; c5 (reduced grid)")
+        extra["c5_interleaving_sweep"] = bench_c5(args, dos, torch, np, ("50", "400"), (8, 64), full_size=True,
+                                                  steps=3, warmup=1, take=1 << 14)
+        extra["c5_interleaving_sweep"]["grid"] = ("reduced: the corners of the 4 x 4 grid (subgroup size 50M and 400M, "
+                                                  "budget 8 and 64 GB); --sweep runs all 16 cells")
     if extra:
         res["extra"] = extra
+    res["bench_wall_s"] = time.perf_counter() - t_start
     print(json.dumps(res), flush=True)
 
 

@@ -141,6 +141,7 @@ class OffloadedState:
         del zeros, tmp
         self.targets = [dos.DOS_ON_CPU] * n_sg
         self.grads_on_host = [True] * n_sg
+        self.host_grads_current = [False] * n_sg      # the pinned / pageable copy equals the device copy
         self.sgs = None
 
     def fill_grads(self, step: int, scales=None, **gkw):
@@ -150,6 +151,7 @@ class OffloadedState:
             sc = 1.0 if scales is None else scales[i]
             S.fill_chunked(lambda start, count: S.grads_bf16(self.seed, step, i, start, count, self.device,
                                                              scale=sc, **gkw), self.g[i])
+            self.host_grads_current[i] = False
 
     def place(self, targets, residents=None, spill_all_grads=False):
         """Build the descriptor array for a plan; move resident state as needed.
@@ -190,10 +192,11 @@ class OffloadedState:
                 dos.dos_host_prefault(lp.data_ptr(), lp.numel() * 2, threads)
 
     def sync_host_grads(self):
-        """Spill the gradients the descriptors expect in pinned host memory."""
+        """Spill the gradients the descriptors expect in host memory (those whose host copy is stale)."""
         for i in range(len(self.sizes)):
-            if self.grads_on_host[i]:
+            if self.grads_on_host[i] and not self.host_grads_current[i]:
                 self.hg[i].copy_(self.g[i], non_blocking=True)
+                self.host_grads_current[i] = True
         torch.cuda.synchronize()
 
     def state(self, i):
@@ -233,6 +236,20 @@ def make_context(n_slots: int, slot_params: int, host_threads: int, *, device="c
     ctx = dos.Context(cfg)
     ctx._keep = (slot_mem, stage)
     return ctx
+
+
+def sample_take(t: torch.Tensor, every: int = 1 << 20, take: int = 1 << 16) -> torch.Tensor:
+    """The elements of the flat tensor `t` at sample_index(len(t), every, take), in that order, gathered
+    with strided views instead of an index list (the sample is runs of `take` consecutive elements)."""
+    n = t.numel()
+    full = n // every
+    parts = []
+    if full:
+        parts.append(t[:full * every].view(full, every)[:, :take].reshape(-1))
+    tail = n - full * every
+    if tail:
+        parts.append(t[full * every:full * every + min(take, tail)])
+    return torch.cat(parts) if len(parts) != 1 else parts[0].clone()
 
 
 def sample_index(n: int, every: int = 1 << 20, take: int = 1 << 16) -> np.ndarray:
