@@ -112,7 +112,7 @@ typedef struct dos_launch_cfg {
                             0 = default, negative = none                           */
   int32_t xcd_group;     /* 0 = block b owns tile b (blocks, and so tiles, go round
                             the 8 XCDs one by one); a power of two k = each XCD takes k
-                            consecutive tiles at a time (layout 4, AdamW only)       */
+                            consecutive tiles at a time (layouts 4-6, AdamW only)    */
 } dos_launch_cfg;
 
 /* ---- device-resident update (Algorithm 1, gpu_update) ---------------------
@@ -134,10 +134,12 @@ dos_status dos_adam_step(const dos_subgroup* sg, const dos_hparams* hp, void* hi
  * accesses, 8-byte bf16), two trips unrolled; 1: one trip; 2: four trips; 3: each
  * lane handles 8 consecutive elements (two 16-byte FP32 accesses, 16-byte bf16);
  * 4: one trip and no tile loop (block b owns tile b and nothing else; grid_blocks
- * must be 0); bit 4 (0x10) makes the loads non-temporal; bits 5-6 pick the store
- * policy: 0x20 non-temporal, 0x40 non-temporal at system scope without the
+ * must be 0); 5, 6: as 4 with two and four trips per lane (a block owns 2 or 4
+ * consecutive bursts of 16 bytes per lane in each array, loaded and stored array by
+ * array; AdamW only); bit 4 (0x10) makes the loads non-temporal; bits 5-6 pick the
+ * store policy: 0x20 non-temporal, 0x40 non-temporal at system scope without the
  * wave-level bit (sc1 nt), 0x60 non-temporal at system scope (sc0 sc1 nt); the two
- * system-scope policies exist in layout 4 only.
+ * system-scope policies exist in layouts 4 to 6 only.
  * dos_adam_step uses variant 0x74 with 64-thread blocks and an LDS request of
  * 14848 bytes per block (11 one-wave blocks per compute unit).  A NULL cfg means
  * those defaults; unknown values, lds_bytes above 65536: DOS_EINVAL.  Adagrad and

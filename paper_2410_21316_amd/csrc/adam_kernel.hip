@@ -179,10 +179,12 @@ __global__ __launch_bounds__(512) void adam_kernel_quads(float* __restrict__ p, 
   adam_tail(p, m, v, g, p_lp, n_quads, n, s);
 }
 
-// Layout A without the tile loop: block b owns quads [b*blockDim, (b+1)*blockDim),
-// nothing else.  The shortest possible wave: five descriptors, four loads, the
-// update, four stores.
-template <bool NTL, int NTS>
+// Layout A without the tile loop: block b owns Q * blockDim quads, nothing else:
+// lane l handles quads l, l + blockDim, ... of the tile, so every load or store
+// instruction of a wave covers 1 KiB of whole lines (512 B for the 16-bit arrays)
+// and the Q instructions for one array follow each other.  Q = 1 is the shortest
+// possible wave: five descriptors, four loads, the update, four stores.
+template <bool NTL, int NTS, int Q>
 __global__ __launch_bounds__(512) void adam_kernel_tile(float* __restrict__ p, float* __restrict__ m,
                                                         float* __restrict__ v, const uint16_t* __restrict__ g,
                                                         uint16_t* __restrict__ p_lp, uint64_t n, AdamScalars s,
@@ -197,21 +199,31 @@ __global__ __launch_bounds__(512) void adam_kernel_tile(float* __restrict__ p, f
     const uint64_t x = t & 7, seq = t >> 3;
     t = ((((seq >> xcd_shift) << 3) + x) << xcd_shift) | (seq & ((1ull << xcd_shift) - 1));
   }
-  const uint64_t e0 = t * blockDim.x * 4;                              // first element of this tile
+  const uint64_t e0 = t * blockDim.x * (4 * Q);                        // first element of this tile
   const uint64_t left = whole > e0 ? whole - e0 : 0;                   // whole-quad elements from e0 on
   const __amdgpu_buffer_rsrc_t rp = tile_rsrc(p + e0, left * 4), rm = tile_rsrc(m + e0, left * 4),
                                rv = tile_rsrc(v + e0, left * 4), rg = tile_rsrc(g + e0, left * 2),
                                ro = tile_rsrc(p_lp + e0, left * 2);
-  const uint32_t off4 = threadIdx.x * 16, off2 = threadIdx.x * 8;
-  const u32x2 G = buf_ld2<NTL>(rg, off2);
-  f32x4 P = buf_ld4<NTL>(rp, off4);
-  f32x4 M = buf_ld4<NTL>(rm, off4);
-  f32x4 V = buf_ld4<NTL>(rv, off4);
-  const u32x2 o = adam_quad(s, P, M, V, G);
-  buf_st4<NTS>(rm, off4, M);
-  buf_st4<NTS>(rv, off4, V);
-  buf_st4<NTS>(rp, off4, P);
-  buf_st2<NTS>(ro, off2, o);
+  u32x2 G[Q], O[Q];
+  f32x4 P[Q], M[Q], V[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) G[q] = buf_ld2<NTL>(rg, (q * blockDim.x + threadIdx.x) * 8);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) P[q] = buf_ld4<NTL>(rp, (q * blockDim.x + threadIdx.x) * 16);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) M[q] = buf_ld4<NTL>(rm, (q * blockDim.x + threadIdx.x) * 16);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) V[q] = buf_ld4<NTL>(rv, (q * blockDim.x + threadIdx.x) * 16);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) O[q] = adam_quad(s, P[q], M[q], V[q], G[q]);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) buf_st4<NTS>(rm, (q * blockDim.x + threadIdx.x) * 16, M[q]);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) buf_st4<NTS>(rv, (q * blockDim.x + threadIdx.x) * 16, V[q]);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) buf_st4<NTS>(rp, (q * blockDim.x + threadIdx.x) * 16, P[q]);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) buf_st2<NTS>(ro, (q * blockDim.x + threadIdx.x) * 8, O[q]);
   adam_tail(p, m, v, g, p_lp, n >> 2, n, s);
 }
 
@@ -306,7 +318,7 @@ __global__ __launch_bounds__(256) void pull_copy_kernel(u32x4* __restrict__ dst,
 template <bool NTL, int NTS>
 dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStream_t st_, float* p, float* m, float* v,
                          const uint16_t* g, uint16_t* lp, uint64_t n, const AdamScalars& s, uint32_t xcd_shift) {
-  if (s.opt != DOS_OPT_ADAMW) {  // the accumulator rules exist in the untiled layout only
+  if (s.opt != DOS_OPT_ADAMW) {  // the accumulator rules exist in the one-quad untiled layout only
     if (layout != 4) return DOS_EINVAL;
     if (s.opt == DOS_OPT_RMSPROP)
       hipLaunchKernelGGL((accum_kernel_tile<true, NTL, NTS>), grid, block, lds, st_, p, v, g, lp, n, s);
@@ -314,9 +326,17 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStrea
       hipLaunchKernelGGL((accum_kernel_tile<false, NTL, NTS>), grid, block, lds, st_, p, v, g, lp, n, s);
     return DOS_OK;
   }
-  if constexpr (NTS >= 2) {  // system-scope stores exist in the untiled layout only
+  if (layout == 5) {
+    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS, 2>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift);
+    return DOS_OK;
+  }
+  if (layout == 6) {
+    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS, 4>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift);
+    return DOS_OK;
+  }
+  if constexpr (NTS >= 2) {  // system-scope stores exist in the untiled layouts only
     if (layout != 4) return DOS_EINVAL;
-    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift);
+    hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS, 1>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift);
     return DOS_OK;
   } else {
   switch (layout) {
@@ -324,7 +344,7 @@ dos_status launch_layout(int layout, dim3 grid, dim3 block, size_t lds, hipStrea
     case 1: hipLaunchKernelGGL((adam_kernel_quads<1, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
     case 2: hipLaunchKernelGGL((adam_kernel_quads<4, NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
     case 3: hipLaunchKernelGGL((adam_kernel_octets<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s); break;
-    case 4: hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift); break;
+    case 4: hipLaunchKernelGGL((adam_kernel_tile<NTL, NTS, 1>), grid, block, lds, st_, p, m, v, g, lp, n, s, xcd_shift); break;
     default: return DOS_EINVAL;
   }
   return DOS_OK;
@@ -354,23 +374,23 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   const int layout = variant & 0xF;
   const bool ntl = (variant & 0x10) != 0;
   const int sp = (variant >> 5) & 3;  // 0 plain, 1 nt, 2 sc1 nt, 3 sc0 sc1 nt
-  if (layout > 4 || (variant & ~0x7F)) return DOS_EINVAL;
-  if (layout == 4 && blocks != 0) return DOS_EINVAL;  // this layout has no tile loop
-  static const int trips_of[5] = {2, 1, 4, 1, 1};
+  if (layout > 6 || (variant & ~0x7F)) return DOS_EINVAL;
+  if (layout >= 4 && blocks != 0) return DOS_EINVAL;  // these layouts have no tile loop
+  static const int trips_of[7] = {2, 1, 4, 1, 1, 2, 4};
   const uint64_t units = (layout == 3) ? (n >> 3) : (n >> 2);
   const uint64_t tile = (uint64_t)threads * trips_of[layout];
   uint64_t n_tiles = (units + tile - 1) / tile;
   if (n_tiles == 0) n_tiles = 1;  // tail only
   if (blocks == 0 || (uint64_t)blocks > n_tiles) blocks = (int64_t)n_tiles;
   if (blocks > 0x7FFFFFFF) {
-    if (layout == 4) return DOS_EINVAL;  // one block per tile: more tiles than a grid can hold
+    if (layout >= 4) return DOS_EINVAL;  // one block per tile: more tiles than a grid can hold
     blocks = 0x7FFFFFFF;                 // grid-stride covers the rest
   }
   // XCD-grouped tile order (untiled AdamW layout only): the grid becomes a multiple of 8 << k
   uint32_t xcd_shift = 32;
   if (cfg && cfg->xcd_group) {
     const int64_t grp = cfg->xcd_group;
-    if (layout != 4 || s.opt != DOS_OPT_ADAMW || grp < 1 || grp > (1 << 20) || (grp & (grp - 1))) return DOS_EINVAL;
+    if (layout < 4 || s.opt != DOS_OPT_ADAMW || grp < 1 || grp > (1 << 20) || (grp & (grp - 1))) return DOS_EINVAL;
     xcd_shift = (uint32_t)__builtin_ctzll((unsigned long long)grp);
     const int64_t unit = 8 * grp;
     blocks = (blocks + unit - 1) / unit * unit;

@@ -61,6 +61,16 @@ def test_untiled_layout_and_wave_cap_give_the_same_bits(variant, threads, lds, h
               zero_pct=5.0, heavy_tail=True)
 
 
+@pytest.mark.parametrize("variant", [5, 0x35, 0x75, 6, 0x56, 0x76])
+@pytest.mark.parametrize("n,threads,lds,group", [(300_007, 0, 0, 0), (5, 64, -1, 0), (1023, 128, 20480, 2),
+                                                 ((1 << 21) + 5, 256, 65536, 0), (262_147, 64, 27000, 16)])
+def test_untiled_layouts_with_two_and_four_quads_per_lane_give_the_same_bits(variant, n, threads, lds, group, hp):
+    """Layouts 5 and 6: a block owns two or four 1 KiB bursts per array instead of one."""
+    run_steps(n, S.BASE_SEED + variant + n, 2, hp,
+              launch=dict(variant=variant, block_threads=threads, grid_blocks=0, lds_bytes=lds, xcd_group=group),
+              zero_pct=5.0, heavy_tail=True)
+
+
 @pytest.mark.parametrize("n", [5, 300_007, (1 << 21) + 5])
 @pytest.mark.parametrize("group", [1, 2, 16, 1024, 1 << 20])
 def test_xcd_grouped_tile_order_gives_the_same_bits(n, group, hp):
