@@ -18,23 +18,52 @@
 // kept), in the order documented in dos.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+
 #include "dos_internal.h"
 #include "tile_access.h"
 
 namespace dos {
 namespace {
 
-// Dynamic LDS requested per 64-thread block of the default launch.  The kernel
-// never touches it: 160 KiB / 14.5 KiB = 11 blocks per CU, i.e. about three waves
-// per SIMD instead of the eight the register count would allow.  Measured on
-// MI355X over 100M-parameter subgroups: 6.7 TB/s with 10-11 waves per CU, 6.05
-// with 32, 6.45 with 9, 4.1 with 5 -- fewer waves keep fewer DRAM pages open at
-// once, too few no longer cover the latency.
+// Dynamic LDS requested per 64-thread block of the default launch, on a compute
+// unit with 160 KiB of LDS (gfx950).  The kernel never touches it: 160 KiB /
+// 14.5 KiB = 11 blocks per CU, i.e. about three waves per SIMD instead of the
+// eight the register count would allow.  Measured on MI355X over 100M-parameter
+// subgroups: 6.7 TB/s with 10-11 waves per CU, 6.05 with 32, 6.45 with 9, 4.1
+// with 5 -- fewer waves keep fewer DRAM pages open at once, too few no longer
+// cover the latency.  On a device that reports another LDS size per compute unit
+// the request is scaled with it, so that the cap stays at the same number of waves.
+constexpr int64_t kLdsPerCuAssumed = 160 * 1024;
 constexpr int64_t kDefaultLdsThrottle = 14848;
 // The two-array rules (Adagrad, RMSProp) move 20 instead of 28 bytes per element, so a
 // wave holds less traffic and the best cap is higher: 15 waves per CU (6.7 TB/s; 6.6 with
 // 11 or 17 waves).
 constexpr int64_t kDefaultLdsThrottleTwoArrays = 10923;
+
+// LDS per compute unit of the current device (queried once per device; the value gfx950
+// has if the query fails).
+int64_t lds_per_cu() {
+  static std::atomic<int64_t> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return kLdsPerCuAssumed;
+  }
+  int64_t v = cache[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int bytes = 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess ||
+        bytes < 64 * 1024) {
+      (void)hipGetLastError();
+      bytes = (int)kLdsPerCuAssumed;
+    }
+    v = bytes;
+    cache[dev].store(v, std::memory_order_relaxed);
+  }
+  return v;
+}
 
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T* ptr) {
@@ -365,9 +394,14 @@ dos_status launch_adam(float* p, float* m, float* v, const uint16_t* g, uint16_t
   int threads = (cfg && cfg->block_threads) ? cfg->block_threads : 64;
   int64_t blocks = cfg ? cfg->grid_blocks : 0;
   // The kernel uses no LDS; a dynamic allocation only caps how many waves a CU holds.
-  int64_t lds = (cfg && cfg->lds_bytes) ? cfg->lds_bytes
-                : s.opt == DOS_OPT_ADAMW     ? kDefaultLdsThrottle
-                                             : kDefaultLdsThrottleTwoArrays;
+  int64_t lds;
+  if (cfg && cfg->lds_bytes) {
+    lds = cfg->lds_bytes;
+  } else {
+    lds = s.opt == DOS_OPT_ADAMW ? kDefaultLdsThrottle : kDefaultLdsThrottleTwoArrays;
+    const int64_t have = lds_per_cu();
+    if (have != kLdsPerCuAssumed) lds = std::min<int64_t>(65536, lds * have / kLdsPerCuAssumed);
+  }
   if (lds < 0) lds = 0;
   if (lds > 65536) return DOS_EINVAL;
   if (variant < 0 || threads < 64 || threads > 512 || (threads % 64) != 0 || blocks < 0) return DOS_EINVAL;
