@@ -45,6 +45,6 @@ def dos_probe_host_stream(p: int, m: int, v: int, g: int, out16: int, n: int, ou
     """Seconds for `reps` sweeps of the host update's access pattern over n elements."""
     sec = C.c_double()
     _b.check(load().dos_probe_host_stream(C.c_void_p(p), C.c_void_p(m), C.c_void_p(v), C.c_void_p(g), C.c_void_p(out16),
-                                          int(n), int(out_n), int(threads), int(reps), int(bool(streamed)),
+                                          int(n), int(out_n), int(threads), int(reps), int(streamed),
                                           C.byref(sec)), "dos_probe_host_stream")
     return sec.value

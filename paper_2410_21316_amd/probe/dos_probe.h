@@ -44,7 +44,9 @@ dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t 
  * and write one 16-bit word per element to out16 -- ordinary host memory of
  * out_n >= n elements (streamed = 0), or a window of out_n elements of device
  * memory that the host writes through the PCIe BAR with non-temporal stores
- * (streamed = 1; each thread rewrites its own part of the window).  *seconds is
+ * (streamed = 1; each thread rewrites its own part of the window), or nowhere
+ * (streamed = 2: the 16-bit words are formed and dropped, which shows what the
+ * output path costs).  *seconds is
  * the wall time of the sweeps: 26 bytes of host memory traffic per element and
  * sweep (28 when out16 is host memory, more where its lines are read before
  * they are written).  The ceiling against which the host lane of the update

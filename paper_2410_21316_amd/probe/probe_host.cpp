@@ -91,7 +91,7 @@ extern "C" dos_status dos_probe_host_stream(float* p, float* m, float* v, const 
           for (uint64_t off = 0; off < cnt; off += kBlock) {
             const uint64_t c = cnt - off < kBlock ? cnt - off : kBlock;
             stream_block(p + lo + off, m + lo + off, v + lo + off, g + lo + off, tmp, c);
-            copy_out(win + ((off / kBlock) % (window / kBlock)) * kBlock, tmp, c);  // window >= 2 blocks
+            if (streamed == 1) copy_out(win + ((off / kBlock) % (window / kBlock)) * kBlock, tmp, c);  // window >= 2 blocks
           }
         }
       });
