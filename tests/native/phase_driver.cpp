@@ -205,6 +205,50 @@ int main() {
     free(slot_mem);
     free(stage);
   }
+  // A phase with more pieces or chunks than the context reserved at creation (16384 and 65536) is
+  // refused before anything is touched, instead of growing the work lists.
+  {
+    const uint64_t n = 64ull * 65537;  // 65537 chunks of 64; 16385 pieces of 256 would need n >= 4194560
+    std::vector<float> p(n, 0.5f), m(n, 0.0f), v(n, 0.0f);
+    std::vector<uint16_t> g(n, 0x3A00), lp(n, 0);
+    void* slot_mem = aligned(2 * 14 * 64);
+    void* stage = aligned(4 * 64 * 2);
+    dos_ctx_config cfg{};
+    cfg.slot_mem = slot_mem;
+    cfg.slot_bytes = 2 * 14 * 64;
+    cfg.slot_params = 64;
+    cfg.n_slots = 2;
+    cfg.host_threads = 2;
+    cfg.pinned_stage = stage;
+    cfg.pinned_stage_bytes = 4 * 64 * 2;
+    cfg.upload_chunk_params = 64;
+    dos_ctx* ctx = nullptr;
+    if (dos_ctx_create(&ctx, &cfg) != DOS_OK) return fail("dos_ctx_create (small slots) failed");
+    dos_subgroup sg{p.data(), m.data(), v.data(), g.data(), lp.data(), n, DOS_HOST_PINNED, DOS_HOST_PINNED};
+    if (((uintptr_t)p.data() | (uintptr_t)m.data() | (uintptr_t)v.data() | (uintptr_t)g.data() | (uintptr_t)lp.data()) & 15)
+      return fail("test arrays are not 16-byte aligned");
+    uint8_t target = DOS_ON_CPU;
+    int32_t order = 0;
+    dos_plan plan{};
+    plan.n_sg = 1;
+    plan.n_slots = 2;
+    plan.slot_params = 64;
+    plan.target = &target;
+    plan.order = &order;
+    dos_hparams hp{1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, 1, 0};
+    if (dos_run_update_phase(ctx, &sg, 1, &plan, &hp, nullptr) != DOS_EBUDGET) return fail("65537 chunks accepted");
+    target = DOS_ON_GPU;
+    if (dos_run_update_phase(ctx, &sg, 1, &plan, &hp, nullptr) != DOS_EBUDGET) return fail("65537 pieces accepted");
+    for (uint64_t k = 0; k < n; k += 4097)
+      if (p[k] != 0.5f || m[k] != 0.0f || lp[k] != 0) return fail("state touched by a refused phase");
+    // one element fewer per list limit is fine: 16384 pieces exactly
+    sg.n = 64ull * 16384;
+    if (dos_run_update_phase(ctx, &sg, 1, &plan, &hp, nullptr) != DOS_OK) return fail("16384 pieces refused");
+    if (p[0] == 0.5f) return fail("accepted phase did nothing");
+    dos_ctx_destroy(ctx);
+    free(slot_mem);
+    free(stage);
+  }
   printf("phase_driver ok\n");
   return 0;
 }
