@@ -21,7 +21,7 @@ constexpr uint64_t kMaxParams = DOS_STAGED_MAX_PARAMS;
 // p | m | v (FP32) | g (16-bit), each kMaxParams elements
 constexpr uint64_t kScratchBytes = 14 * kMaxParams;
 
-__device__ __align__(256) unsigned char scratch[kScratchBytes];
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kMaxDevices = 64;
 std::mutex g_mu;
