@@ -10,9 +10,9 @@ the 7B-parameter resident state (70 x 100M), the 13B-parameter host-offloaded
 state (130 x 100M, 40 GB GPU budget) run through dos_plan_subgroups +
 dos_run_update_phase (with the host lane's 16-bit output stored straight into
 device memory where the machine allows; then the pinned part of it through the
-GPU lane alone, the whole once more through the pinned ring, and under six
-schedules), the corners of the subgroup-size x budget grid, and Adagrad /
-RMSProp on the primary workload's shape.
+GPU lane alone and with 2 and 4 host threads, the whole once more through the
+pinned ring, and under six schedules), the corners of the subgroup-size x budget
+grid, and Adagrad / RMSProp on the primary workload's shape.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra c1,c3,c4,c5,rules|none] [--upload auto|direct|pull|dma]
                     [--rule adamw|adagrad|rmsprop] [--schedule balanced|stride|all_cpu|all_gpu|fixed:N]
