@@ -766,9 +766,8 @@ def bench_c4(args, dos, torch, np):
                         "ceiling_plain_stream": ceil,
                         "ceiling_same_kernel_standalone_GBps": same_kernel,
                         "ceiling_note": "the higher of two same-run measurements: a plain stream of the same access "
-                                        "pattern, and the host update itself with all threads over a 1.9 GB buffer "
-                                        "(dos_calibrate); the arithmetic of the update paces its memory requests, and on "
-                                        "this host that reaches more bandwidth than the plain stream does",
+                                        "pattern, and the host update itself with all threads over a buffer of 470 MB "
+                                        "per thread (dos_calibrate)",
                         "traffic_model": "26 B per host-updated parameter with direct uploads (reads 4+4+4+2, writes "
                                          "4+4+4; the 16-bit output leaves through the BAR), 28 B through the ring; "
                                          "24 B per staged parameter (read by the prefetch, written by the flush)"}

@@ -340,12 +340,16 @@ dos_status dos_run_update_phase(dos_ctx* ctx, dos_subgroup* sgs, int32_t n_sg, c
  *                      slot 0 and the upload ring -- or, for a context without a
  *                      ring, pinned memory obtained for the duration of the call;
  *   gpu_params_per_s, launch_overhead_s   the fused kernel over one slot;
- *   cpu_params_per_s   the host update with all worker threads over a temporary
- *                      1.9 GB host buffer (larger than the caches), its 16-bit
- *                      output going where the phases send it: with
- *                      DOS_CTX_UPLOAD_DIRECT into device memory through the PCIe
- *                      BAR (the staging slots serve as the target), otherwise
- *                      into host memory as into the upload ring.
+ *   cpu_params_per_s   the host update with all worker threads, taking chunks
+ *                      from a shared counter as the phases' workers do, over a
+ *                      temporary host buffer of 16 Mi parameters per thread
+ *                      (470 MB each, 7.5 GB for 16 threads: far beyond the
+ *                      caches -- a buffer of 1.9 GB still reads 13 % too fast
+ *                      on a many-chiplet host), its 16-bit output going where
+ *                      the phases send it: with DOS_CTX_UPLOAD_DIRECT into
+ *                      device memory through the PCIe BAR (the staging slots
+ *                      serve as the target), otherwise into host memory as into
+ *                      the upload ring.
  * The rates are stand-alone peaks: what staged traffic takes away from the host
  * cores when both lanes run (Section 5.4, CPU cores per GPU) is left to
  * dos_cost_model_observe.  Not part of the update phase: the call allocates and

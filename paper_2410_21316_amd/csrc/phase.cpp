@@ -933,15 +933,22 @@ dos_status calibrate(dos_ctx* c, dos_cost_model* out) {
   // ---- host update with all worker threads, through the path the phase will use: with direct
   // uploads the 16-bit output is stored into device memory through the PCIe BAR (here: into the
   // staging slots, every thread rewriting its own window of them), otherwise it goes to host memory
-  // as it does into the upload ring.  The state is a temporary buffer far larger than any last-level
-  // cache (64 Mi parameters, 1.9 GB): on this machine's host the cores sit on several chiplets with
-  // 32 MiB of L3 each, and anything ring-sized reads three to four times the rate a real subgroup
-  // reaches.
+  // as it does into the upload ring.  The threads take 1 Mi-parameter chunks from a shared counter, as
+  // the phase's workers take theirs, sweep after sweep over a temporary buffer of 16 Mi parameters per
+  // thread (470 MB; 7.5 GB for 16 threads; at least 64 Mi parameters).  The footprint matters: on this
+  // machine's host every core has tens of MiB of last-level cache within reach, a 1.9 GB buffer swept
+  // again and again by 16 threads reads 13 % faster than the tens of GB a phase streams through (18.2
+  // against 16.1 G params/s), and a ring-sized one three to four times faster.
   {
     const bool direct = (c->flags & DOS_CTX_UPLOAD_DIRECT) != 0;
     const int T = c->T;
-    uint64_t n = (uint64_t)64 << 20;
-    char* big = static_cast<char*>(aligned_alloc(4096, n * 28));
+    uint64_t n = std::min<uint64_t>((uint64_t)512 << 20, std::max<uint64_t>((uint64_t)64 << 20, (uint64_t)T << 24));
+    char* big = nullptr;
+    constexpr uint64_t kHuge = (uint64_t)2 << 20;  // 2 MiB-aligned, so that the kernel can back it with huge pages
+    while (!(big = static_cast<char*>(aligned_alloc(kHuge, (n * 28 + kHuge - 1) & ~(kHuge - 1)))) &&
+           n > ((uint64_t)64 << 20))
+      n >>= 1;
+    if (big) (void)dos_host_advise_hugepages(big, n * 28);  // before the first touch; a refusal costs 2 %
     char* base = big;
     if (!big) {
       if (c->ring_n < 2) return DOS_ENOMEM;
@@ -962,8 +969,13 @@ dos_status calibrate(dos_ctx* c, dos_cost_model* out) {
     uint16_t* lp = g + n;
     dos::AdamScalars sc{0.9f, 0.999f, 0.1f, 0.001f, 1e-3f, 1.0f, 1e-8f, 1.0f, DOS_OPT_ADAMW};
     const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
-    // every thread sweeps its own slice `reps` times; reps == 0 fills it (first touch by its owner)
-    auto run = [&](int reps) {
+    const uint64_t chunk = (uint64_t)1 << 20, n_chunks = (n + chunk - 1) / chunk;
+    std::atomic<uint64_t> next{0};
+    // sweeps == 0: every thread fills its own slice (first touch by one owner per region);
+    // otherwise the threads share out `sweeps` passes over all chunks
+    auto run = [&](int sweeps) {
+      next.store(0);
+      const uint64_t total = n_chunks * (uint64_t)sweeps;
       std::vector<std::thread> th;
       th.reserve(T);
       struct Joiner {  // threads already started are joined also when starting the next one fails
@@ -974,31 +986,33 @@ dos_status calibrate(dos_ctx* c, dos_cost_model* out) {
         }
       } joiner{th};
       for (int t = 0; t < T; ++t) {
-        const uint64_t lo = (uint64_t)t * per;
-        if (lo >= n) break;
-        const uint64_t cnt = std::min(per, n - lo);
-        th.emplace_back([=] {
-          if (reps == 0) {
-            for (uint64_t i = lo; i < lo + cnt; ++i) {
+        th.emplace_back([&, t] {
+          if (sweeps == 0) {
+            const uint64_t lo = (uint64_t)t * per;
+            for (uint64_t i = lo; i < std::min(n, lo + per); ++i) {
               p[i] = 0.01f;
               m[i] = v[i] = 0.0f;
               g[i] = (uint16_t)(0x3A00 + (i & 127));
               lp[i] = 0;
             }
+            return;
           }
-          for (int r = 0; r < reps; ++r) {
+          uint16_t* const win = dev_out + (uint64_t)t * window;
+          for (;;) {
+            const uint64_t k = next.fetch_add(1, std::memory_order_relaxed);
+            if (k >= total) break;
+            const uint64_t lo = (k % n_chunks) * chunk, cnt = std::min(chunk, n - lo);
             if (!direct) {
               dos::host_adam_range(p + lo, m + lo, v + lo, g + lo, lp + lo, cnt, sc);
               continue;
             }
-            uint16_t* const win = dev_out + (uint64_t)t * window;
             for (uint64_t off = 0; off < cnt; off += window)
               dos::host_adam_range_streamed(p + lo + off, m + lo + off, v + lo + off, g + lo + off, win,
                                             std::min(window, cnt - off), sc);
           }
-          if (direct && reps > 0) {  // drain the posted writes, as the phase's workers do
+          if (direct) {  // drain the posted writes, as the phase's workers do
             dos::store_fence();
-            (void)*reinterpret_cast<volatile uint16_t*>(dev_out + (uint64_t)t * window);
+            (void)*reinterpret_cast<volatile uint16_t*>(win);
           }
         });
       }
@@ -1006,17 +1020,16 @@ dos_status calibrate(dos_ctx* c, dos_cost_model* out) {
     double rate = 0;
     try {
       run(0);
-      run(1);
       auto a = clk::now();
-      run(2);
-      const double t2 = secs(a, clk::now());
-      // three measurements of ~0.2 s each; the rate is a stand-alone peak, so the best one counts
-      // (on a shared host single measurements scatter by tens of percent)
-      const int hreps = (int)std::max(2.0, std::min(400.0, 0.2 / (t2 / 2.0)));
+      run(1);
+      const double t1 = secs(a, clk::now());
+      // three measurements of ~0.25 s each; the rate is a stand-alone peak, so the best one counts
+      // (on a shared host single measurements scatter)
+      const int sweeps = (int)std::max(1.0, std::min(400.0, 0.25 / t1));
       for (int k = 0; k < 3; ++k) {
         a = clk::now();
-        run(hreps);
-        rate = std::max(rate, (double)n * hreps / secs(a, clk::now()));
+        run(sweeps);
+        rate = std::max(rate, (double)n * sweeps / secs(a, clk::now()));
       }
     } catch (...) {
       if (big) free(big);

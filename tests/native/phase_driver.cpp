@@ -72,6 +72,9 @@ dos_status launch_pull_copy_u16(uint16_t* dst, const uint16_t* src, uint64_t n, 
 }
 }  // namespace dos
 
+// (api.cpp, where the real one lives, is not part of this build)
+extern "C" dos_status dos_host_advise_hugepages(void*, uint64_t) { return DOS_OK; }
+
 static int fail(const char* what) {
   fprintf(stderr, "phase_driver: %s\n", what);
   return 1;
