@@ -452,33 +452,39 @@ class OracleShare:
 
 def host_stream_ceiling(dos, torch, np, host_threads, direct):
     """Host-memory stream with the host update's access pattern and (almost) no arithmetic, in the same
-    run and with the same thread count: the ceiling the host lane is judged against.  Reads p, m, v, g and
-    rewrites p, m, v of a 64 Mi-parameter buffer (1.9 GB, far beyond the caches); the 16-bit output goes
-    through the PCIe BAR into device memory (direct uploads) or into host memory (ring uploads)."""
+    run, measured the way dos_calibrate measures the update itself: chunks from a shared counter over a buffer
+    of 16 Mi parameters per thread (7.5 GB for 16 threads, far beyond the host's caches), about a quarter of a
+    second per measurement, best of three, for the phase's thread count and for three quarters and half of it.
+    Reads p, m, v, g and rewrites p, m, v; the 16-bit output goes through the PCIe BAR into device memory
+    (direct uploads) or into host memory (ring uploads)."""
     from paper_2410_21316_amd import probe
-    n = 64 << 20
+    n = max(64 << 20, min(512 << 20, host_threads << 24))
     arrs = [torch.empty(n, dtype=torch.float32) for _ in range(3)] + [torch.empty(n, dtype=torch.int16)]
     for t in arrs:
+        dos.dos_host_advise_hugepages(t.data_ptr(), t.numel() * t.element_size())
         dos.dos_host_prefault(t.data_ptr(), t.numel() * t.element_size(), host_threads)
         t.zero_()
+    out_n = 64 << 20
     if direct:
-        out = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+        out = torch.zeros(out_n, dtype=torch.int16, device="cuda:0")
         torch.cuda.synchronize()
-        dos.dos_host_prefault(out.data_ptr(), n * 2, host_threads)      # map the device pages for the host
+        dos.dos_host_prefault(out.data_ptr(), out_n * 2, host_threads)      # map the device pages for the host
     else:
-        out = torch.zeros(n, dtype=torch.int16)
+        out, out_n = torch.zeros(n, dtype=torch.int16), n
     ptrs = [t.data_ptr() for t in arrs]
     bpp = 26 if direct else 28
     by_threads = {}
     for T in sorted({max(1, host_threads // 2), max(1, host_threads * 3 // 4), host_threads}):
-        probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, n, T, 1, direct)                   # warm-up
-        best = min(probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, n, T, 3, direct) / 3 for _ in range(3))
+        t1 = probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, out_n, T, 1, direct)         # warm-up, and its time
+        reps = max(1, min(400, int(0.25 / t1)))
+        best = min(probe.dos_probe_host_stream(*ptrs, out.data_ptr(), n, out_n, T, reps, direct) / reps
+                   for _ in range(3))
         by_threads[T] = bpp * n / best / 1e9
     top = max(by_threads, key=by_threads.get)
     return {"GBps": by_threads[top], "threads_at_best": top, "GBps_by_threads": by_threads, "bytes_per_param": bpp,
             "what": "plain stream of the host update's access pattern (read p, m, v, g; rewrite p, m, v; 16-bit output "
-                    + ("stored through the PCIe BAR" if direct else "to host memory") + "), 64 Mi parameters, best of "
-                    "3 x 3 sweeps per thread count, same run"}
+                    + ("stored through the PCIe BAR" if direct else "to host memory") + f"), {n >> 20} Mi parameters in "
+                    "1 Mi chunks from a shared counter, best of three quarter-second measurements per thread count, same run"}
 
 
 def calibrate_peaks(ctx, log, tag, rule):

@@ -39,18 +39,20 @@ dos_status dos_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, vo
 dos_status dos_probe_adam_traffic(const dos_subgroup* sg, int32_t mode, int32_t lds_bytes, void* hip_stream);
 
 /* Host-memory stream with the access pattern of the host update and no
- * arithmetic to speak of: `threads` threads each sweep their slice of
- * p, m, v (FP32, read and rewritten in place) and g (16-bit, read) `reps` times
- * and write one 16-bit word per element to out16 -- ordinary host memory of
- * out_n >= n elements (streamed = 0), or a window of out_n elements of device
- * memory that the host writes through the PCIe BAR with non-temporal stores
- * (streamed = 1; each thread rewrites its own part of the window), or nowhere
- * (streamed = 2: the 16-bit words are formed and dropped, which shows what the
- * output path costs).  *seconds is
- * the wall time of the sweeps: 26 bytes of host memory traffic per element and
- * sweep (28 when out16 is host memory, more where its lines are read before
- * they are written).  The ceiling against which the host lane of the update
- * phase is judged.  Synchronous; allocates only its threads. */
+ * arithmetic to speak of: `threads` threads share out `reps` passes over
+ * p, m, v (FP32, read and rewritten in place) and g (16-bit, read) in chunks of
+ * 1 Mi elements taken from a common counter (as the workers of the update phase
+ * take theirs) and write one 16-bit word per element to out16 -- ordinary host
+ * memory of out_n >= n elements (streamed = 0), a window of out_n elements of
+ * device memory that the host writes through the PCIe BAR with non-temporal
+ * stores (streamed = 1; each thread rewrites its own part of the window), or
+ * nowhere (streamed = 2: the 16-bit words are formed and dropped, which shows
+ * what the output path costs).  *seconds is the wall time of all passes: 26
+ * bytes of host memory traffic per element and pass (28 when out16 is host
+ * memory, more where its lines are read before they are written).  Use a
+ * buffer far beyond the host's caches (hundreds of MB per thread) and enough
+ * passes for a few tenths of a second.  The ceiling against which the host lane
+ * of the update phase is judged.  Synchronous; allocates only its threads. */
 dos_status dos_probe_host_stream(float* p, float* m, float* v, const uint16_t* g, uint16_t* out16, uint64_t n,
                                  uint64_t out_n, int32_t threads, int32_t reps, int32_t streamed, double* seconds);
 

@@ -6,6 +6,7 @@
 #include <immintrin.h>
 #endif
 
+#include <atomic>
 #include <chrono>
 #include <thread>
 #include <vector>
@@ -68,30 +69,36 @@ extern "C" dos_status dos_probe_host_stream(float* p, float* m, float* v, const 
     return DOS_EINVAL;
   if (!streamed && out_n < n) return DOS_EINVAL;
   const int T = threads;
-  const uint64_t per = (((n + T - 1) / T) + 63) & ~(uint64_t)63;
-  const uint64_t window = (out_n / (uint64_t)T) & ~(uint64_t)63;  // per thread, streamed output only
-  if (streamed && window < 4096) return DOS_EBUDGET;
+  constexpr uint64_t kChunk = (uint64_t)1 << 20;  // the threads take chunks from a shared counter, as the phase's workers do
+  constexpr uint64_t kBlock = 2048;               // 4 KiB of output: stays in the first-level cache
+  const uint64_t n_chunks = (n + kChunk - 1) / kChunk, total = n_chunks * (uint64_t)reps;
+  const uint64_t window = (out_n / (uint64_t)T) & ~(uint64_t)(kBlock - 1);  // per thread, streamed output only
+  if (streamed && window < 2 * kBlock) return DOS_EBUDGET;
   try {
+    std::atomic<uint64_t> next{0};
     std::vector<std::thread> pool;
     pool.reserve(T);
     const auto t0 = std::chrono::steady_clock::now();
     for (int t = 0; t < T; ++t) {
-      const uint64_t lo = (uint64_t)t * per;
-      if (lo >= n) break;
-      const uint64_t cnt = per < n - lo ? per : n - lo;
-      pool.emplace_back([=] {
-        constexpr uint64_t kBlock = 2048;  // 4 KiB of output: stays in the first-level cache
+      pool.emplace_back([&, t] {
         alignas(64) uint16_t tmp[kBlock];
-        for (int r = 0; r < reps; ++r) {
+        uint16_t* const win = out16 + (uint64_t)t * window;
+        uint64_t wpos = 0;
+        for (;;) {
+          const uint64_t k = next.fetch_add(1, std::memory_order_relaxed);
+          if (k >= total) break;
+          const uint64_t lo = (k % n_chunks) * kChunk, cnt = kChunk < n - lo ? kChunk : n - lo;
           if (!streamed) {
             stream_block(p + lo, m + lo, v + lo, g + lo, out16 + lo, cnt);
             continue;
           }
-          uint16_t* const win = out16 + (uint64_t)t * window;
           for (uint64_t off = 0; off < cnt; off += kBlock) {
             const uint64_t c = cnt - off < kBlock ? cnt - off : kBlock;
             stream_block(p + lo + off, m + lo + off, v + lo + off, g + lo + off, tmp, c);
-            if (streamed == 1) copy_out(win + ((off / kBlock) % (window / kBlock)) * kBlock, tmp, c);  // window >= 2 blocks
+            if (streamed == 1) {
+              copy_out(win + wpos, tmp, c);
+              wpos = wpos + 2 * kBlock <= window ? wpos + kBlock : 0;
+            }
           }
         }
       });
@@ -103,4 +110,3 @@ extern "C" dos_status dos_probe_host_stream(float* p, float* m, float* v, const 
   }
   return DOS_OK;
 }
-
