@@ -210,6 +210,29 @@ def test_other_rules_through_the_phase(optimizer, hp):
     assert stats.h2d_bytes == 8.0 * staged + 2.0 * on_cpu + 2.0 * spilled
 
 
+@pytest.mark.parametrize("flags", ["dma", "spin", "dma+spin", "spin+direct", "profile+dma"])
+def test_upload_and_wait_modes_give_the_same_bits(flags, hp):
+    """The other ways a context can be told to work -- 16-bit uploads by hipMemcpyAsync instead of the copy
+    kernel, spinning instead of sleeping waits -- change timing only: a mixed plan with pieces, host and device
+    gradients stays bit-identical to the oracle."""
+    f = 0
+    if "dma" in flags:
+        f |= dos.DOS_CTX_UPLOAD_DMA
+    if "spin" in flags:
+        f |= dos.DOS_CTX_SPIN_WAIT
+    if "profile" in flags:
+        f |= dos.DOS_CTX_PROFILE
+    if "direct" in flags:
+        if not dos.dos_device_large_bar(0):
+            pytest.skip("the device memory is not mapped into the host's address space")
+        f |= dos.DOS_CTX_UPLOAD_DIRECT
+    targets = [1, 0, 1, 0, 0, 1, 0, 1, 0]
+    stats = run_phase_case(SIZES, targets, list(reversed(range(len(SIZES)))), 3, 1 << 17, hp, steps=2,
+                           grad_on_device=[1, 0, 0, 0, 0, 1, 0, 0, 0], host_threads=3, chunk_params=1 << 14,
+                           ring_chunks=5, flags=f, zero_pct=5.0, heavy_tail=True, seed=S.BASE_SEED + 33)
+    assert stats.params_gpu == sum(n for n, t in zip(SIZES, targets) if t)
+
+
 def test_all_gpu_and_all_cpu_plans(hp):
     run_phase_case(SIZES, [1] * len(SIZES), None, 3, 1 << 18, hp, steps=2)
     run_phase_case(SIZES, [0] * len(SIZES), None, 0, 1 << 18, hp, steps=2)
