@@ -68,6 +68,27 @@ def test_static_staging_matches_the_update_phase_on_two_calls_in_a_row(optimizer
             b.free()
 
 
+def test_static_staging_of_a_two_array_rule_needs_no_first_moment(hp):
+    """Adagrad keeps p and v only: the m pointer may be NULL, m is neither staged nor touched, and a
+    subgroup of exactly the maximum size fits."""
+    n = dos.DOS_STAGED_MAX_PARAMS
+    st = OffloadedState([n], S.BASE_SEED + 95, grad_on_device=[False])
+    try:
+        st.host[0]["m"][:] = 7.0                              # a canary: must survive
+        sg = st.sgs[0]
+        no_m = dos.subgroup(sg.p, 0, sg.v, sg.g, sg.p_lp, sg.n, dos.DOS_HOST_PINNED, dos.DOS_HOST_PINNED)
+        for step in (1, 2):
+            st.set_grads(step)
+            dos.dos_gpu_update_staged(no_m, dos.hparams(step=step, optimizer="adagrad", **hp))
+            torch.cuda.synchronize()
+            st.oracle_step(hp, step, optimizer="adagrad")
+        assert np.all(st.host[0]["m"] == 7.0)
+        st.ref[0][1][:] = 7.0
+        st.check("adagrad through the static staging array, m NULL")
+    finally:
+        st.free()
+
+
 def test_static_staging_rejects_what_does_not_fit_and_what_it_cannot_reach(hp):
     lib = dos.load()
     h = dos.hparams(step=1, **hp)
