@@ -583,9 +583,11 @@ def run_interleaved(dos, torch, np, sizes, budget_bytes, steps, warmup, host_thr
              "h2d_span_s": st.h2d_span_s, "d2h_span_s": st.d2h_span_s,
              "duplex_overlap_s": st.duplex_overlap_s, "cpu_lane_s": st.cpu_lane_s, "gpu_lane_s": st.gpu_lane_s,
              "host_update_params_per_s": st.params_cpu / st.cpu_lane_s if st.cpu_lane_s > 0 else None,
-             # host memory traffic of the phase: 26 B (28 through the ring) per host-updated parameter, and
-             # every staged byte is read from or written to host memory once
-             "host_dram_GBps": ((26.0 if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT else 28.0) * st.params_cpu
+             # host memory traffic of the phase: 26 B per host-updated parameter (18 for the rules without a
+             # first moment; 2 more through the ring), and every staged byte is read from or written to host
+             # memory once
+             "host_dram_GBps": (((26.0 if rule == "adamw" else 18.0)
+                                 + (0.0 if upload_flags & dos.DOS_CTX_UPLOAD_DIRECT else 2.0)) * st.params_cpu
                                 + 2.0 * staged) / st.wall_s / 1e9,
              "lower_bound_s": lb_plan, "ratio_to_lower_bound": st.wall_s / lb_plan if lb_plan > 0 else None,
              "ratio_to_nominal_link_bound": st.wall_s / lb_nominal if lb_nominal > 0 else None,
@@ -763,8 +765,10 @@ def bench_c4(args, dos, torch, np):
                             "others are in pageable host memory and are planned CPU-only")
     # the roofline that governs the executed plan when it keeps (most of) the work on the host cores:
     # host memory bandwidth, against a plain stream of the same access pattern measured in this run
-    ceil = host_stream_ceiling(dos, torch, np, args.host_threads, direct)
-    bpp_host = 26.0 if direct else 28.0
+    # (the plain stream has AdamW's access pattern; with another rule only the stand-alone update is a ceiling)
+    ceil = (host_stream_ceiling(dos, torch, np, args.host_threads, direct) if args.rule == "adamw"
+            else {"GBps": 0.0, "threads_at_best": None, "what": "not measured for this rule"})
+    bpp_host = (26.0 if args.rule == "adamw" else 18.0) + (0.0 if direct else 2.0)
     same_kernel = out["host_rate_calibrated"] * bpp_host / 1e9
     ceiling = max(ceil["GBps"], same_kernel)
     out["host_dram"] = {"bound": "host memory bandwidth", "achieved_GBps": out["host_dram_GBps"],
