@@ -781,6 +781,10 @@ def bench_c4(args, dos, torch, np):
                         "traffic_model": "26 B per host-updated parameter with direct uploads (reads 4+4+4+2, writes "
                                          "4+4+4; the 16-bit output leaves through the BAR), 28 B through the ring; "
                                          "24 B per staged parameter (read by the prefetch, written by the flush)"}
+    if args.rule != "adamw":
+        # dos_calibrate and the plain stream both measure AdamW's access pattern: no ceiling for other rules
+        out["host_dram"].update({"ceiling_GBps": None, "frac": None, "ceiling_same_kernel_standalone_GBps": None,
+                                 "ceiling_note": "the ceilings are measured with AdamW's access pattern only"})
     log(f"[c4] host memory: phase {out['host_dram_GBps']:.0f} GB/s; ceilings: plain stream {ceil['GBps']:.0f} GB/s "
         f"({ceil['threads_at_best']} threads), the update itself stand-alone {same_kernel:.0f} GB/s")
     out.pop("_cost_model", None)
