@@ -487,6 +487,47 @@ def host_stream_ceiling(dos, torch, np, host_threads, direct):
                     "1 Mi chunks from a shared counter, best of three quarter-second measurements per thread count, same run"}
 
 
+class HostMemoryLoad:
+    """The plain stream of host_stream_ceiling (host memory only: 28 B per parameter), kept running on
+    `threads` threads in the background between start() and stop(): what the host lane of a ring-upload phase
+    does to the host's memory while the link is working.  stop() returns the stream's own rate in GB/s."""
+
+    def __init__(self, dos, torch, threads):
+        from paper_2410_21316_amd import probe
+        self.probe, self.threads = probe, threads
+        self.n = n = max(64 << 20, min(512 << 20, threads << 24))
+        self.arrs = [torch.empty(n, dtype=torch.float32) for _ in range(3)] + [torch.empty(n, dtype=torch.int16)
+                                                                                for _ in range(2)]
+        for t in self.arrs:
+            dos.dos_host_advise_hugepages(t.data_ptr(), t.numel() * t.element_size())
+            dos.dos_host_prefault(t.data_ptr(), t.numel() * t.element_size(), threads)
+            t.zero_()
+        self.ptrs = [t.data_ptr() for t in self.arrs]
+        t1 = self._sweeps(1)
+        self.reps = max(1, min(400, int(0.1 / t1)))
+        self.thread = None
+
+    def _sweeps(self, reps):
+        return self.probe.dos_probe_host_stream(*self.ptrs, self.n, self.n, self.threads, reps, 0)
+
+    def start(self):
+        import threading
+        self.halt, self.sweeps, self.busy_s = False, 0, 0.0
+
+        def loop():
+            while not self.halt:
+                self.busy_s += self._sweeps(self.reps)
+                self.sweeps += self.reps
+        self.thread = threading.Thread(target=loop, daemon=True)
+        self.thread.start()
+
+    def stop(self):
+        self.halt = True
+        self.thread.join()
+        self.thread = None
+        return 28.0 * self.n * self.sweeps / max(self.busy_s, 1e-9) / 1e9
+
+
 def calibrate_peaks(ctx, log, tag, rule):
     """dos_calibrate twice; each rate keeps the better of the two (they are peaks: bounds are priced with them)."""
     cms = [ctx.dos_calibrate() for _ in range(2)]
@@ -811,6 +852,27 @@ def bench_c4(args, dos, torch, np):
         out_lane["steps"] = [{k: r[k] for k in ("wall_s", "h2d_GBps", "d2h_GBps", "ratio_to_lower_bound",
                                                 "duplex_overlap_s", "h2d_busy_s", "d2h_busy_s", "h2d_span_s",
                                                 "d2h_span_s", "timed")} for r in lane["steps"]]
+        # The same lane once more while all host threads stream through host memory (the access pattern of the
+        # host lane with ring uploads, on buffers of its own): what a saturated host memory leaves of the link.
+        load = HostMemoryLoad(dos, torch, args.host_threads)
+        load.start()
+        try:
+            loaded = run_interleaved(dos, torch, np, sizes, budget, steps=2, warmup=1, host_threads=args.host_threads,
+                                     gkw={}, seed=None, check=True, share=share, tag="c4 gpu lane, host memory busy",
+                                     state=state, rule=args.rule, schedule="all_gpu", adapt=False, only=pinned,
+                                     fresh_grads="keep", cm=dos.cost_model(*out["calibrated"]))
+        finally:
+            stream_GBps = load.stop()
+        del load
+        out_lane["with_host_memory_busy"] = {
+            "what": f"the same phases while {args.host_threads} other threads stream through host memory (read p, m, v, g; "
+                    "rewrite p, m, v; 16-bit output to host memory; 1 warm-up + 2 timed phases)",
+            "update_phase_s_per_iter": loaded["update_phase_s_per_iter"], "h2d_GBps": loaded["h2d_GBps"],
+            "d2h_GBps": loaded["d2h_GBps"], "ratio_to_lower_bound": loaded["ratio_to_lower_bound"],
+            "host_stream_GBps_meanwhile": stream_GBps,
+            "sample_mismatches_vs_oracle": loaded["sample_mismatches_vs_oracle"]}
+        log(f"[c4 gpu lane, host memory busy] {loaded['update_phase_s_per_iter']:.3f} s per phase, H2D "
+            f"{loaded['h2d_GBps']:.1f} GB/s, D2H {loaded['d2h_GBps']:.1f} GB/s, the host stream at {stream_GBps:.0f} GB/s meanwhile")
         out["gpu_lane_only"] = out_lane
     if "few_cores" in legs:
         # The regime the paper works in: host cores that update far less than the link can stage (its testbed:
