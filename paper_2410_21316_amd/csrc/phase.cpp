@@ -155,8 +155,12 @@ hipError_t library_streams(int device, hipStream_t out[4]) {
   DeviceStreams& d = g_streams[device];
   if (!d.made) {
     for (int i = 0; i < 4; ++i) {
+      if (d.s[i]) continue;  // made by an earlier call that failed further on
       hipError_t e = hipStreamCreateWithFlags(&d.s[i], hipStreamNonBlocking);
-      if (e != hipSuccess) return e;
+      if (e != hipSuccess) {
+        d.s[i] = nullptr;
+        return e;
+      }
     }
     d.made = true;
   }
