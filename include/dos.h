@@ -317,7 +317,8 @@ void dos_ctx_destroy(dos_ctx* ctx);
  * (state_loc == DOS_DEVICE) are updated in place, last; CPU-planned subgroups
  * (state and gradients in pinned or pageable host memory) are updated in place
  * by the host worker threads, which write the 16-bit parameters into the pinned
- * upload ring and send them to p_lp on the upload stream.  hp->optimizer selects
+ * upload ring and send them to p_lp on the upload stream (or store them straight
+ * into p_lp, DOS_CTX_UPLOAD_DIRECT).  n_sg may be at most 65536.  hp->optimizer selects
  * the rule for all of them; Adagrad and RMSProp stage and flush p and v only.
  * Synchronous at the boundary: on return every p, m, v is back where state_loc
  * says and every p_lp has landed on the device.  plan->target decides the lane
